@@ -1,0 +1,180 @@
+"""Plain fp64 CPU definition of the CPM-2-MoE feed-forward layer.
+
+TEST INFRASTRUCTURE ONLY.  Nothing on the product path may import this module;
+it exists so that tests, the smoke check and the bench's CPU-baseline leg have
+an independent statement of what the layer computes.  It shares no code with
+the HIP kernels.
+
+What it states (CPM-2 paper, arxiv 2106.10715):
+
+* Section 2.1: the feed-forward layer of every Transformer block is expanded
+  to several experts, and each token is sent to an expert chosen from its own
+  hidden state by a gating function.
+* Section 2.3 (MoE stage): the gate is a frozen random projection of the hidden
+  state; all experts start as copies of the dense feed-forward layer.
+* Table 1: d_model 4096, d_ff 10240.  The printed parameter totals (11 B dense,
+  198 B with 32 experts) are only reproduced by a three-matrix gated expert
+  (see model_parameter_count), so an expert is
+      FFN_e(x) = (GELU(x W_gate[e]) * (x W_in[e])) W_out[e],   no biases.
+* Section 6.2: tokens are routed and batched by expert before computation.
+  Offloading and scheduling change where and when an expert runs, never the
+  result, so the streamed mode has the same definition as the resident one.
+
+Every floating-point step is evaluated in float64 from the stored-precision
+inputs.  Readings of points the paper leaves open: selection is on the logits,
+general top-k (k=1 is the paper's case), ties go to the lower expert index,
+slots are ordered by descending logit, combine weights are the softmax over the
+selected k (renorm=1; a single expert then has weight exactly 1) or the full
+softmax probability (renorm=0), GELU is the exact erf form, and no token is
+dropped.
+
+Pinned by tests/test_oracle_*.py (brute-force loops, dense special cases, hand
+computed values, invariants).
+"""
+from __future__ import annotations
+
+import math
+from typing import Callable, NamedTuple, Optional, Tuple
+
+import numpy as np
+from scipy.special import erf as _erf
+
+
+class Routing(NamedTuple):
+    idx: np.ndarray      # [T, k] int32, selected experts, slot j ordered by descending logit
+    w: np.ndarray        # [T, k] float32 combine weights
+    logits: np.ndarray   # [T, E] float64
+    margin: np.ndarray   # [T] float64: smallest gap between consecutive ranks 0..k of the sorted logits
+
+
+class Permutation(NamedTuple):
+    counts: np.ndarray   # [E] int32
+    offsets: np.ndarray  # [E+1] int32, exclusive prefix sum of counts
+    perm: np.ndarray     # [A] int32: perm[row] = flat assignment index a = t*k + j
+    inv: np.ndarray      # [A] int32: inv[a] = row
+    Xp: np.ndarray       # [A, d] float64: Xp[row] = x[perm[row] // k]
+
+
+def gelu(z: np.ndarray) -> np.ndarray:
+    """Exact GELU: z * Phi(z), Phi the standard normal CDF."""
+    z = np.asarray(z, dtype=np.float64)
+    return 0.5 * z * (1.0 + _erf(z / math.sqrt(2.0)))
+
+
+def gelu_tanh(z: np.ndarray) -> np.ndarray:
+    """The tanh approximation of GELU (offered as act=1; never mixed with the exact form)."""
+    z = np.asarray(z, dtype=np.float64)
+    return 0.5 * z * (1.0 + np.tanh(math.sqrt(2.0 / math.pi) * (z + 0.044715 * z ** 3)))
+
+
+def _act(act: int) -> Callable[[np.ndarray], np.ndarray]:
+    if act == 0:
+        return gelu
+    if act == 1:
+        return gelu_tanh
+    raise ValueError("act must be 0 (erf GELU) or 1 (tanh GELU)")
+
+
+def gate_logits(x: np.ndarray, Wg: np.ndarray, bias: Optional[np.ndarray] = None) -> np.ndarray:
+    """L[t, e] = sum_i x[t, i] Wg[i, e] (+ b[e]): the random-projection gate of Section 2.3."""
+    L = np.asarray(x, dtype=np.float64) @ np.asarray(Wg, dtype=np.float64)
+    if bias is not None:
+        L = L + np.asarray(bias, dtype=np.float64)[None, :]
+    return L
+
+
+def route(x: np.ndarray, Wg: np.ndarray, k: int = 1, bias: Optional[np.ndarray] = None,
+          renorm: int = 1) -> Routing:
+    """Gate each token to its k best experts (Section 2.1: one expert per token, k = 1)."""
+    L = gate_logits(x, Wg, bias)
+    T, E = L.shape
+    if not 1 <= k <= E:
+        raise ValueError("need 1 <= k <= E")
+    # stable sort of -L: descending logit, equal logits keep ascending expert index
+    order = np.argsort(-L, axis=1, kind="stable")
+    idx = order[:, :k].astype(np.int32)
+    top = np.take_along_axis(L, order[:, :min(k + 1, E)], axis=1)
+    if top.shape[1] > 1:
+        margin = (top[:, :-1] - top[:, 1:]).min(axis=1)
+    else:
+        margin = np.full(T, np.inf)
+    sel = top[:, :k]
+    if renorm:
+        ex = np.exp(sel - sel[:, :1])
+        w = ex / ex.sum(axis=1, keepdims=True)
+    else:
+        m = L.max(axis=1, keepdims=True)
+        ex = np.exp(L - m)
+        w = np.take_along_axis(ex, idx.astype(np.int64), axis=1) / ex.sum(axis=1, keepdims=True)
+    return Routing(idx, w.astype(np.float32), L, margin)
+
+
+def permute(x: np.ndarray, idx: np.ndarray, E: int) -> Permutation:
+    """Batch the assignments by expert (Section 6.2), keeping flat order a = t*k + j inside an expert."""
+    T, k = idx.shape
+    flat = idx.reshape(-1).astype(np.int64)
+    counts = np.bincount(flat, minlength=E).astype(np.int32)
+    offsets = np.zeros(E + 1, dtype=np.int32)
+    np.cumsum(counts, out=offsets[1:])
+    perm = np.argsort(flat, kind="stable").astype(np.int32)   # rows: experts ascending, a ascending
+    inv = np.empty(T * k, dtype=np.int32)
+    inv[perm] = np.arange(T * k, dtype=np.int32)
+    Xp = np.asarray(x, dtype=np.float64)[perm // k] if T * k else np.zeros((0, x.shape[1]))
+    return Permutation(counts, offsets, perm, inv, Xp)
+
+
+def expert_ffn_rows(X: np.ndarray, W_in: np.ndarray, W_gate: np.ndarray, W_out: np.ndarray,
+                    act: int = 0) -> np.ndarray:
+    """One expert applied to rows X[n, d]: (act(X W_gate) * (X W_in)) W_out."""
+    X = np.asarray(X, dtype=np.float64)
+    a = X @ np.asarray(W_gate, dtype=np.float64)
+    b = X @ np.asarray(W_in, dtype=np.float64)
+    h = _act(act)(a) * b
+    return h @ np.asarray(W_out, dtype=np.float64)
+
+
+ExpertSource = Callable[[int], Tuple[np.ndarray, np.ndarray, np.ndarray]]  # e -> (W_in, W_gate, W_out)
+
+
+def expert_ffn(Xp: np.ndarray, offsets: np.ndarray, experts: ExpertSource, act: int = 0) -> np.ndarray:
+    """Yp[r] = FFN_e(Xp[r]) for every row r of expert e's segment; empty experts are never touched."""
+    A, d = Xp.shape
+    Yp = np.zeros((A, d), dtype=np.float64)
+    for e in range(len(offsets) - 1):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        if hi > lo:
+            W_in, W_gate, W_out = experts(e)
+            Yp[lo:hi] = expert_ffn_rows(Xp[lo:hi], W_in, W_gate, W_out, act)
+    return Yp
+
+
+def combine(Yp: np.ndarray, inv: np.ndarray, w: np.ndarray) -> np.ndarray:
+    """y[t] = sum_j w[t, j] Yp[inv[t*k + j]]: the selected experts' outputs replace the FFN output."""
+    T, k = w.shape
+    y = np.zeros((T, Yp.shape[1]), dtype=np.float64)
+    w64 = np.asarray(w, dtype=np.float64)
+    inv2 = np.asarray(inv).reshape(T, k)
+    for j in range(k):
+        y += w64[:, j:j + 1] * Yp[inv2[:, j]]
+    return y
+
+
+def layer_forward(x: np.ndarray, Wg: np.ndarray, experts: ExpertSource, E: int, k: int = 1,
+                  bias: Optional[np.ndarray] = None, renorm: int = 1, act: int = 0):
+    """The whole layer: route -> batch by expert -> expert FFNs -> weighted un-permute."""
+    r = route(x, Wg, k, bias, renorm)
+    p = permute(x, r.idx, E)
+    Yp = expert_ffn(p.Xp, p.offsets, experts, act)
+    y = combine(Yp, p.inv, r.w)
+    return y, r, p, Yp
+
+
+def model_parameter_count(n_experts: int = 1, ffn_matrices: int = 3, d: int = 4096, f: int = 10240,
+                          layers: int = 24) -> int:
+    """Weights in the encoder-decoder stack of Table 1 (embeddings and norms left out).
+
+    Encoder block: self-attention (4 d^2) + FFN; decoder block: self- and cross-attention
+    (8 d^2) + FFN; every FFN holds n_experts experts of ffn_matrices d-by-f matrices.
+    """
+    ffn = n_experts * ffn_matrices * d * f
+    return layers * (4 * d * d + ffn) + layers * (8 * d * d + ffn)
