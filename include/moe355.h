@@ -1,0 +1,163 @@
+/*
+ * moe355 -- the Mixture-of-Experts feed-forward layer of CPM-2-MoE on one AMD MI355X (gfx950).
+ *
+ * What the layer is (CPM-2, arxiv 2106.10715):
+ *   - Section 2.1: the feed-forward layer of each Transformer block is expanded to several
+ *     experts; every token is sent to an expert selected from its hidden state by a gate.
+ *   - Section 2.3 (MoE stage): the gate is a frozen random projection of the hidden state.
+ *   - Table 1: d_model 4096, d_ff 10240; the printed totals (11 B / 198 B parameters) fix a
+ *     three-matrix gated expert:  FFN_e(x) = (GELU(x W_gate[e]) * (x W_in[e])) W_out[e].
+ *   - Section 6 (InfMoE): tokens are routed and batched by expert before computation; expert
+ *     parameters may live in CPU memory and be loaded while other experts compute, on separate
+ *     streams, with at most K experts resident on the device.
+ *
+ * Conventions for every entry point
+ *   - C ABI, plain pointers and sizes.  "device" = pointer into this GPU's memory, "host" =
+ *     ordinary host pointer, "pinned" = host memory allocated with hipHostMalloc.
+ *   - All matrices are row-major and contiguous.  dtype selects the storage type of x, W_g, the
+ *     expert weights, Xp, Yp and y (MOE_F32 or MOE_BF16); accumulation is always fp32.
+ *     idx/counts/offsets/perm/inv are int32; gate weights w and the gate bias are fp32.
+ *   - The caller owns every buffer.  The library never allocates or frees device memory; scratch
+ *     is the caller's workspace `ws` of at least moe_workspace_bytes() bytes, 256-byte aligned.
+ *     (Only moe_stream_ctx_create allocates: one copy stream, a few events and a small pinned
+ *     host buffer, all released by moe_stream_ctx_destroy.)
+ *   - Calls are asynchronous: work is enqueued on `stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream) and the call returns.  The one exception is moe_layer_forward in
+ *     streamed mode, which waits once for the per-expert token counts (see there).
+ *   - Return value: MOE_OK or a negative MOE_ERR_* code; moe_last_error() then returns a message
+ *     (thread-local, valid until the next failing call on the same thread).  Nothing is printed,
+ *     no exception crosses the boundary.  Arguments are validated before anything is launched.
+ *   - Limits: d and f multiples of 64; 1 <= k <= min(E, 8); 1 <= E <= 256; T >= 0 (T = 0 is a
+ *     legal no-op); T*k*max(d,f) < 2^31.  Inputs must be finite.
+ */
+#ifndef MOE355_H
+#define MOE355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { MOE_OK = 0, MOE_ERR_INVALID_ARG = -1, MOE_ERR_UNSUPPORTED = -2, MOE_ERR_WORKSPACE = -3, MOE_ERR_HIP = -4 };
+enum { MOE_F32 = 0, MOE_BF16 = 1 };
+
+typedef struct moe_cfg {
+    int32_t T;       /* tokens */
+    int32_t d;       /* d_model */
+    int32_t f;       /* d_ff */
+    int32_t E;       /* experts */
+    int32_t k;       /* experts per token; the paper's layer uses 1 */
+    int32_t dtype;   /* MOE_F32 | MOE_BF16 */
+    int32_t renorm;  /* 1: combine weights = softmax over the k selected logits (k = 1 -> exactly 1.0)
+                        0: combine weights = full-softmax probability of each selected expert */
+    int32_t act;     /* 0: exact GELU z*Phi(z);  1: tanh approximation of GELU */
+} moe_cfg;
+
+typedef struct moe_stream_ctx moe_stream_ctx;   /* opaque: state of the host-streamed expert mode */
+
+/* Message of the last failing call on this thread ("" if none). */
+const char* moe_last_error(void);
+
+/* Bytes of workspace that any entry point needs for this cfg (moe_layer_forward is the largest user). */
+int moe_workspace_bytes(const moe_cfg* cfg, size_t* bytes);
+
+/* Bytes of one expert in packed form (3*d*f elements of dtype). */
+int moe_expert_bytes(const moe_cfg* cfg, size_t* bytes);
+
+/*
+ * Rewrite one expert's three matrices (Table 1 shape; weights are frozen at inference, Section 2.3)
+ * into the packed block the FFN kernels read: all experts have the same size (Section 6.2), so a
+ * packed expert is one contiguous block of moe_expert_bytes() and "loading an expert" is one copy.
+ *   W_in_e, W_gate_e [d, f], W_out_e [f, d]: device, row-major, dtype.
+ *   packed_e: device, moe_expert_bytes() bytes, 256-byte aligned, must not overlap the inputs.
+ * Packed layout, bf16: up block, then down block.  Up block: for each 32-column group n of d_ff and
+ * each 16-row step s of d_model, a 1 KiB W_gate fragment then a 1 KiB W_in fragment; down block: for
+ * each 32-column group of d_model and each 16-row step of d_ff one 1 KiB W_out fragment.  A fragment
+ * holds W[16 s + 8 (l / 32) + j, 32 n + l % 32] at element 8 l + j (l = 0..63, j = 0..7), i.e. the
+ * operand order of the 32x32x16 bf16 matrix instruction.  fp32: W_gate, W_in, W_out concatenated,
+ * row-major, unchanged.
+ */
+int moe_pack_weights(const moe_cfg* cfg, const void* W_in_e, const void* W_gate_e, const void* W_out_e,
+                     void* packed_e, void* stream);
+
+/*
+ * Gate (Sections 2.1, 2.3): logits L = x W_g (+ gate_bias); per token the k largest logits, slot j
+ * ordered by descending logit, every tie resolved to the lower expert index; combine weights per
+ * cfg->renorm.  The selection equals the one exact arithmetic on the stored inputs would make: tokens
+ * whose fp32 logits are closer than the fp32 error bound are re-evaluated in fp64 inside the kernel.
+ *   x [T, d], W_g [d, E]: device, dtype.   gate_bias [E]: device fp32, or NULL.
+ *   idx [T, k] int32, w [T, k] fp32: device, written.
+ */
+int moe_route(const moe_cfg* cfg, const void* x, const void* W_g, const float* gate_bias,
+              int32_t* idx, float* w, void* ws, void* stream);
+
+/*
+ * Batch assignments by expert (Section 6.2).  Assignment a = t*k + j goes to expert idx[a].
+ *   counts[e] = number of assignments of e; offsets = exclusive prefix sum (offsets[E] = T*k);
+ *   rows are ordered by expert, then by ascending a (stable, deterministic);
+ *   perm[row] = a, inv[a] = row, Xp[row, :] = x[perm[row] / k, :].
+ *   x [T, d] device dtype; idx [T, k] device (values must lie in [0, E): out-of-range values are
+ *   clamped into range rather than trusted); counts [E], offsets [E+1], perm [T*k], inv [T*k] int32
+ *   and Xp [T*k, d] dtype: device, written.  Xp may be NULL (index outputs only).
+ */
+int moe_permute(const moe_cfg* cfg, const void* x, const int32_t* idx,
+                int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv, void* Xp,
+                void* ws, void* stream);
+
+/*
+ * Expert FFNs on the batched rows: for every expert e with offsets[e] < offsets[e+1] and every row r
+ * in that range, Yp[r] = (act(Xp[r] W_gate[e]) * (Xp[r] W_in[e])) W_out[e].  Experts without rows
+ * are not read.  The d_ff-wide intermediate is kept in ws in dtype.
+ *   Xp [T*k, d] device dtype; offsets [E+1] device int32 (read on the device, no host sync);
+ *   W_packed: device, E packed experts back to back (moe_pack_weights); Yp [T*k, d] device, written.
+ */
+int moe_expert_ffn(const moe_cfg* cfg, const void* Xp, const int32_t* offsets, const void* W_packed,
+                   void* Yp, void* ws, void* stream);
+
+/*
+ * Weighted un-permute: y[t, :] = sum_{j<k} w[t, j] * Yp[inv[t*k + j], :], summed in slot order in
+ * fp32, rounded once to dtype.   Yp [T*k, d], inv [T*k], w [T, k]: device;  y [T, d]: device, written.
+ */
+int moe_combine(const moe_cfg* cfg, const void* Yp, const int32_t* inv, const float* w, void* y, void* stream);
+
+/*
+ * The whole layer, x -> y, as route -> permute -> expert FFNs -> combine on `stream`; every
+ * intermediate lives in ws.
+ *   Resident mode (sctx == NULL): W_packed holds all E packed experts on the device; nothing waits
+ *   on the host.
+ *   Streamed mode (sctx != NULL, W_packed ignored): the experts live in pinned host memory (Section 6).
+ *   After route + permute the call copies counts[E] to the host and waits for it (the host must know
+ *   which experts have tokens; Section 6.2 sizes an expert's compute by its token count), then for each
+ *   non-empty expert, in ascending id, copies its packed block into one of the K device slots on the
+ *   context's copy stream while earlier experts compute on `stream`; events order copy-before-compute
+ *   and compute-before-slot-reuse.  Experts without tokens are not loaded.  Every call reloads every
+ *   non-empty expert.  The call returns with the remaining work enqueued on `stream`.
+ *   Results are bitwise identical in both modes.
+ */
+int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const float* gate_bias,
+                      const void* W_packed, moe_stream_ctx* sctx, void* y, void* ws, void* stream);
+
+/*
+ * Streamed-mode state (Section 6.2: K experts resident at once, separate streams for loading and
+ * computing).  host_experts: pinned, E packed experts back to back, expert_bytes each (must equal
+ * moe_expert_bytes).  dev_slots: device, K * expert_bytes, 256-byte aligned.  1 <= K <= 16.
+ * Both buffers stay owned by the caller and must outlive the context.  Must be called with the
+ * device that holds dev_slots current.
+ */
+int moe_stream_ctx_create(const moe_cfg* cfg, const void* host_experts, size_t expert_bytes,
+                          void* dev_slots, int32_t K, moe_stream_ctx** out);
+int moe_stream_ctx_destroy(moe_stream_ctx* sctx);
+
+/*
+ * Figures of the last streamed moe_layer_forward on this context; waits for that call's work to
+ * finish.  n_loaded = experts copied; bytes = n_loaded * expert_bytes; copy_ms = first copy start to
+ * last copy end on the copy stream.  Any pointer may be NULL.
+ */
+int moe_stream_ctx_stats(moe_stream_ctx* sctx, int32_t* n_loaded, size_t* bytes, float* copy_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE355_H */

@@ -1,0 +1,290 @@
+// C-ABI entry points of the moe355 library: argument checks, workspace carving, and the host
+// side of the two execution modes of the layer (CPM-2 Section 6: experts resident on the device, or
+// kept in CPU memory and loaded on a second stream while earlier experts compute).
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "common.h"
+
+namespace moe {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+void clear_error() { g_err[0] = '\0'; }
+
+int check_cfg(const moe_cfg* c) {
+    if (c == nullptr) return fail(MOE_ERR_INVALID_ARG, "cfg is NULL");
+    if (c->dtype != MOE_F32 && c->dtype != MOE_BF16) return fail(MOE_ERR_INVALID_ARG, "dtype must be MOE_F32 or MOE_BF16");
+    if (c->T < 0) return fail(MOE_ERR_INVALID_ARG, "T must be >= 0 (got %d)", c->T);
+    if (c->d <= 0 || c->d % 64 != 0) return fail(MOE_ERR_INVALID_ARG, "d must be a positive multiple of 64 (got %d)", c->d);
+    if (c->f <= 0 || c->f % 64 != 0) return fail(MOE_ERR_INVALID_ARG, "f must be a positive multiple of 64 (got %d)", c->f);
+    if (c->E < 1 || c->E > 256) return fail(MOE_ERR_INVALID_ARG, "E must be in [1, 256] (got %d)", c->E);
+    if (c->k < 1 || c->k > 8 || c->k > c->E) return fail(MOE_ERR_INVALID_ARG, "k must be in [1, min(E, 8)] (got %d)", c->k);
+    if (c->renorm != 0 && c->renorm != 1) return fail(MOE_ERR_INVALID_ARG, "renorm must be 0 or 1");
+    if (c->act != 0 && c->act != 1) return fail(MOE_ERR_INVALID_ARG, "act must be 0 (erf GELU) or 1 (tanh GELU)");
+    const long long A = static_cast<long long>(c->T) * c->k;
+    const long long widest = c->d > c->f ? c->d : c->f;
+    if (A * widest >= (1LL << 31)) return fail(MOE_ERR_INVALID_ARG, "T*k*max(d,f) must stay below 2^31");
+    return MOE_OK;
+}
+
+WsLayout ws_layout(const moe_cfg& c) {
+    const size_t A = static_cast<size_t>(c.T) * c.k, es = elem_size(c);
+    const size_t chunks = (A + kPermChunk - 1) / kPermChunk;
+    WsLayout L;
+    size_t at = 0;
+    auto take = [&at](size_t bytes) { const size_t o = at; at += align256(bytes); return o; };
+    L.H = take(A * c.f * es);
+    L.Xp = take(A * c.d * es);
+    L.Yp = take(A * c.d * es);
+    L.idx = take(A * 4);
+    L.w = take(A * 4);
+    L.counts = take(static_cast<size_t>(c.E) * 4);
+    L.offsets = take(static_cast<size_t>(c.E + 1) * 4);
+    L.perm = take(A * 4);
+    L.inv = take(A * 4);
+    L.chunk_hist = take((chunks > 0 ? chunks : 1) * c.E * 4);
+    L.total = at > 0 ? at : 256;
+    return L;
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+struct moe_stream_ctx {
+    moe_cfg cfg;
+    const char* host_experts;
+    size_t expert_bytes;
+    char* dev_slots;
+    int K;
+    int device;
+    hipStream_t copy_stream;
+    hipEvent_t loaded[16];     // copy into slot s finished
+    hipEvent_t released[16];   // compute that read slot s finished
+    bool released_valid[16];
+    hipEvent_t first_copy, last_copy;
+    bool timed;
+    int32_t* h_counts;         // pinned [256]
+    int n_loaded;
+};
+
+#define REQUIRE(ptr, name) \
+    if ((ptr) == nullptr) return fail(MOE_ERR_INVALID_ARG, "%s is NULL", name)
+#define REQUIRE_ALIGNED(ptr, name) \
+    if (!aligned16(ptr)) return fail(MOE_ERR_INVALID_ARG, "%s must be 16-byte aligned", name)
+
+extern "C" {
+
+const char* moe_last_error(void) { return g_err; }
+
+int moe_workspace_bytes(const moe_cfg* cfg, size_t* bytes) {
+    if (int rc = check_cfg(cfg)) return rc;
+    REQUIRE(bytes, "bytes");
+    *bytes = ws_layout(*cfg).total;
+    return MOE_OK;
+}
+
+int moe_expert_bytes(const moe_cfg* cfg, size_t* bytes) {
+    if (int rc = check_cfg(cfg)) return rc;
+    REQUIRE(bytes, "bytes");
+    *bytes = 3 * static_cast<size_t>(cfg->d) * cfg->f * elem_size(*cfg);
+    return MOE_OK;
+}
+
+int moe_pack_weights(const moe_cfg* cfg, const void* W_in_e, const void* W_gate_e, const void* W_out_e,
+                     void* packed_e, void* stream) {
+    if (int rc = check_cfg(cfg)) return rc;
+    REQUIRE(W_in_e, "W_in_e"); REQUIRE(W_gate_e, "W_gate_e"); REQUIRE(W_out_e, "W_out_e"); REQUIRE(packed_e, "packed_e");
+    REQUIRE_ALIGNED(W_in_e, "W_in_e"); REQUIRE_ALIGNED(W_gate_e, "W_gate_e"); REQUIRE_ALIGNED(W_out_e, "W_out_e");
+    REQUIRE_ALIGNED(packed_e, "packed_e");
+    return launch_pack(*cfg, W_in_e, W_gate_e, W_out_e, packed_e, static_cast<hipStream_t>(stream));
+}
+
+int moe_route(const moe_cfg* cfg, const void* x, const void* W_g, const float* gate_bias, int32_t* idx, float* w,
+              void* ws, void* stream) {
+    (void)ws;
+    if (int rc = check_cfg(cfg)) return rc;
+    REQUIRE(W_g, "W_g");
+    if (cfg->T > 0) { REQUIRE(x, "x"); REQUIRE(idx, "idx"); REQUIRE(w, "w"); }
+    return launch_route(*cfg, x, W_g, gate_bias, idx, w, static_cast<hipStream_t>(stream));
+}
+
+int moe_permute(const moe_cfg* cfg, const void* x, const int32_t* idx, int32_t* counts, int32_t* offsets,
+                int32_t* perm, int32_t* inv, void* Xp, void* ws, void* stream) {
+    if (int rc = check_cfg(cfg)) return rc;
+    REQUIRE(counts, "counts"); REQUIRE(offsets, "offsets"); REQUIRE(ws, "ws");
+    if (cfg->T > 0) {
+        REQUIRE(idx, "idx"); REQUIRE(perm, "perm"); REQUIRE(inv, "inv");
+        if (Xp != nullptr) { REQUIRE(x, "x"); REQUIRE_ALIGNED(x, "x"); REQUIRE_ALIGNED(Xp, "Xp"); }
+    }
+    const WsLayout L = ws_layout(*cfg);
+    return launch_permute(*cfg, x, idx, counts, offsets, perm, inv, Xp,
+                          reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.chunk_hist),
+                          static_cast<hipStream_t>(stream));
+}
+
+int moe_expert_ffn(const moe_cfg* cfg, const void* Xp, const int32_t* offsets, const void* W_packed, void* Yp,
+                   void* ws, void* stream) {
+    if (int rc = check_cfg(cfg)) return rc;
+    REQUIRE(offsets, "offsets");
+    if (cfg->T == 0) return MOE_OK;
+    REQUIRE(Xp, "Xp"); REQUIRE(W_packed, "W_packed"); REQUIRE(Yp, "Yp"); REQUIRE(ws, "ws");
+    REQUIRE_ALIGNED(Xp, "Xp"); REQUIRE_ALIGNED(W_packed, "W_packed"); REQUIRE_ALIGNED(Yp, "Yp"); REQUIRE_ALIGNED(ws, "ws");
+    const WsLayout L = ws_layout(*cfg);
+    size_t eb = 0;
+    moe_expert_bytes(cfg, &eb);
+    return launch_expert_ffn(*cfg, Xp, offsets, 0, cfg->E, W_packed, eb, static_cast<long>(cfg->T) * cfg->k,
+                             static_cast<char*>(ws) + L.H, Yp, static_cast<hipStream_t>(stream));
+}
+
+int moe_combine(const moe_cfg* cfg, const void* Yp, const int32_t* inv, const float* w, void* y, void* stream) {
+    if (int rc = check_cfg(cfg)) return rc;
+    if (cfg->T == 0) return MOE_OK;
+    REQUIRE(Yp, "Yp"); REQUIRE(inv, "inv"); REQUIRE(w, "w"); REQUIRE(y, "y");
+    REQUIRE_ALIGNED(Yp, "Yp"); REQUIRE_ALIGNED(y, "y");
+    return launch_combine(*cfg, Yp, inv, w, y, static_cast<hipStream_t>(stream));
+}
+
+int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const float* gate_bias,
+                      const void* W_packed, moe_stream_ctx* sctx, void* y, void* ws, void* stream) {
+    if (int rc = check_cfg(cfg)) return rc;
+    REQUIRE(W_g, "W_g");
+    if (sctx == nullptr) { REQUIRE(W_packed, "W_packed (resident mode)"); REQUIRE_ALIGNED(W_packed, "W_packed"); }
+    if (sctx != nullptr && memcmp(&sctx->cfg, cfg, sizeof(int32_t) * 2) != 0 &&
+        (sctx->cfg.d != cfg->d || sctx->cfg.f != cfg->f || sctx->cfg.E != cfg->E || sctx->cfg.dtype != cfg->dtype))
+        return fail(MOE_ERR_INVALID_ARG, "stream context was created for another d/f/E/dtype");
+    if (cfg->T == 0) return MOE_OK;
+    REQUIRE(x, "x"); REQUIRE(y, "y"); REQUIRE(ws, "ws");
+    REQUIRE_ALIGNED(x, "x"); REQUIRE_ALIGNED(y, "y");
+    if ((reinterpret_cast<uintptr_t>(ws) & 255) != 0) return fail(MOE_ERR_WORKSPACE, "ws must be 256-byte aligned");
+
+    const moe_cfg& c = *cfg;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const WsLayout L = ws_layout(c);
+    char* base = static_cast<char*>(ws);
+    int32_t* idx = reinterpret_cast<int32_t*>(base + L.idx);
+    float* w = reinterpret_cast<float*>(base + L.w);
+    int32_t* counts = reinterpret_cast<int32_t*>(base + L.counts);
+    int32_t* offsets = reinterpret_cast<int32_t*>(base + L.offsets);
+    int32_t* perm = reinterpret_cast<int32_t*>(base + L.perm);
+    int32_t* inv = reinterpret_cast<int32_t*>(base + L.inv);
+    const long A = static_cast<long>(c.T) * c.k;
+    size_t eb = 0;
+    moe_expert_bytes(cfg, &eb);
+
+    if (int rc = launch_route(c, x, W_g, gate_bias, idx, w, s)) return rc;
+    if (int rc = launch_permute(c, x, idx, counts, offsets, perm, inv, base + L.Xp,
+                                reinterpret_cast<int32_t*>(base + L.chunk_hist), s))
+        return rc;
+
+    if (sctx == nullptr) {
+        if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, 0, c.E, W_packed, eb, A, base + L.H, base + L.Yp, s))
+            return rc;
+    } else {
+        // The host has to know which experts hold tokens (and how many) before it can queue loads.
+        MOE_HIP_CHECK(hipMemcpyAsync(sctx->h_counts, counts, sizeof(int32_t) * c.E, hipMemcpyDeviceToHost, s));
+        MOE_HIP_CHECK(hipStreamSynchronize(s));
+        int i = 0;
+        for (int e = 0; e < c.E; ++e) {
+            const int n_e = sctx->h_counts[e];
+            if (n_e <= 0) continue;                       // experts without tokens are never loaded
+            const int slot = i % sctx->K;
+            char* dst = sctx->dev_slots + static_cast<size_t>(slot) * eb;
+            // the load may not overwrite a slot an earlier expert (of this or the previous call) still reads
+            if (sctx->released_valid[slot]) MOE_HIP_CHECK(hipStreamWaitEvent(sctx->copy_stream, sctx->released[slot], 0));
+            if (i == 0) MOE_HIP_CHECK(hipEventRecord(sctx->first_copy, sctx->copy_stream));
+            MOE_HIP_CHECK(hipMemcpyAsync(dst, sctx->host_experts + static_cast<size_t>(e) * eb, eb, hipMemcpyHostToDevice,
+                                         sctx->copy_stream));
+            MOE_HIP_CHECK(hipEventRecord(sctx->loaded[slot], sctx->copy_stream));
+            MOE_HIP_CHECK(hipStreamWaitEvent(s, sctx->loaded[slot], 0));
+            if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, e, 1, dst, eb, n_e, base + L.H, base + L.Yp, s))
+                return rc;
+            MOE_HIP_CHECK(hipEventRecord(sctx->released[slot], s));
+            sctx->released_valid[slot] = true;
+            ++i;
+        }
+        if (i > 0) MOE_HIP_CHECK(hipEventRecord(sctx->last_copy, sctx->copy_stream));
+        sctx->n_loaded = i;
+        sctx->timed = i > 0;
+    }
+    return launch_combine(c, base + L.Yp, inv, w, y, s);
+}
+
+int moe_stream_ctx_create(const moe_cfg* cfg, const void* host_experts, size_t expert_bytes, void* dev_slots,
+                          int32_t K, moe_stream_ctx** out) {
+    if (int rc = check_cfg(cfg)) return rc;
+    REQUIRE(out, "out");
+    *out = nullptr;
+    REQUIRE(host_experts, "host_experts"); REQUIRE(dev_slots, "dev_slots");
+    if (K < 1 || K > 16) return fail(MOE_ERR_INVALID_ARG, "K must be in [1, 16] (got %d)", K);
+    size_t eb = 0;
+    moe_expert_bytes(cfg, &eb);
+    if (expert_bytes != eb)
+        return fail(MOE_ERR_INVALID_ARG, "expert_bytes is %zu but a packed expert of this cfg has %zu", expert_bytes, eb);
+    if ((reinterpret_cast<uintptr_t>(dev_slots) & 255) != 0) return fail(MOE_ERR_INVALID_ARG, "dev_slots must be 256-byte aligned");
+    moe_stream_ctx* ctx = new (std::nothrow) moe_stream_ctx();
+    if (ctx == nullptr) return fail(MOE_ERR_HIP, "out of host memory");
+    memset(ctx, 0, sizeof(*ctx));
+    ctx->cfg = *cfg;
+    ctx->host_experts = static_cast<const char*>(host_experts);
+    ctx->expert_bytes = eb;
+    ctx->dev_slots = static_cast<char*>(dev_slots);
+    ctx->K = K;
+    hipError_t e = hipGetDevice(&ctx->device);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->copy_stream, hipStreamNonBlocking);
+    for (int i = 0; i < K && e == hipSuccess; ++i) {
+        e = hipEventCreateWithFlags(&ctx->loaded[i], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->released[i], hipEventDisableTiming);
+    }
+    if (e == hipSuccess) e = hipEventCreate(&ctx->first_copy);
+    if (e == hipSuccess) e = hipEventCreate(&ctx->last_copy);
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&ctx->h_counts), 256 * sizeof(int32_t), hipHostMallocDefault);
+    if (e != hipSuccess) {
+        const int rc = fail(MOE_ERR_HIP, "creating the stream context failed: %s", hipGetErrorString(e));
+        moe_stream_ctx_destroy(ctx);
+        return rc;
+    }
+    *out = ctx;
+    return MOE_OK;
+}
+
+int moe_stream_ctx_destroy(moe_stream_ctx* ctx) {
+    if (ctx == nullptr) return MOE_OK;
+    if (ctx->copy_stream) { (void)hipStreamSynchronize(ctx->copy_stream); (void)hipStreamDestroy(ctx->copy_stream); }
+    for (int i = 0; i < 16; ++i) {
+        if (ctx->loaded[i]) (void)hipEventDestroy(ctx->loaded[i]);
+        if (ctx->released[i]) (void)hipEventDestroy(ctx->released[i]);
+    }
+    if (ctx->first_copy) (void)hipEventDestroy(ctx->first_copy);
+    if (ctx->last_copy) (void)hipEventDestroy(ctx->last_copy);
+    if (ctx->h_counts) (void)hipHostFree(ctx->h_counts);
+    delete ctx;
+    return MOE_OK;
+}
+
+int moe_stream_ctx_stats(moe_stream_ctx* ctx, int32_t* n_loaded, size_t* bytes, float* copy_ms) {
+    REQUIRE(ctx, "sctx");
+    float ms = 0.f;
+    if (ctx->timed) {
+        MOE_HIP_CHECK(hipEventSynchronize(ctx->last_copy));
+        MOE_HIP_CHECK(hipEventElapsedTime(&ms, ctx->first_copy, ctx->last_copy));
+    }
+    if (n_loaded) *n_loaded = ctx->n_loaded;
+    if (bytes) *bytes = static_cast<size_t>(ctx->n_loaded) * ctx->expert_bytes;
+    if (copy_ms) *copy_ms = ms;
+    return MOE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,70 @@
+// Shared host-side declarations of the moe355 library: error reporting, argument checks,
+// workspace layout and the launchers each stage file defines.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "moe355.h"
+
+namespace moe {
+
+// Records a message for moe_last_error() and returns `code`.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
+#define MOE_HIP_CHECK(expr)                                                                   \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess)                                                                 \
+            return ::moe::fail(MOE_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_));   \
+    } while (0)
+
+#define MOE_LAUNCH_CHECK(name)                                                                \
+    do {                                                                                      \
+        hipError_t e_ = hipGetLastError();                                                    \
+        if (e_ != hipSuccess)                                                                 \
+            return ::moe::fail(MOE_ERR_HIP, "launch of %s failed: %s", name, hipGetErrorString(e_)); \
+    } while (0)
+
+int check_cfg(const moe_cfg* cfg);
+
+inline size_t elem_size(const moe_cfg& c) { return c.dtype == MOE_BF16 ? 2 : 4; }
+inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+// Assignments handled by one block of the histogram / scatter kernels of the permutation.
+constexpr int kPermChunk = 1024;
+// Rows of one expert segment covered by one block of the FFN kernels.
+constexpr int kTileM = 128;
+
+// Byte offsets of every region inside the caller's workspace.
+struct WsLayout {
+    size_t H;          // [A, f] dtype: gated intermediate of the expert FFNs
+    size_t Xp;         // [A, d] dtype
+    size_t Yp;         // [A, d] dtype
+    size_t idx;        // [A] int32
+    size_t w;          // [A] fp32
+    size_t counts;     // [E] int32
+    size_t offsets;    // [E+1] int32
+    size_t perm;       // [A] int32
+    size_t inv;        // [A] int32
+    size_t chunk_hist; // [chunks, E] int32: per-chunk expert histograms, then per-chunk bases
+    size_t total;
+};
+WsLayout ws_layout(const moe_cfg& c);
+
+// ---- launchers (each enqueues on `s` and returns MOE_OK or an error already recorded) ----
+int launch_route(const moe_cfg& c, const void* x, const void* Wg, const float* bias, int32_t* idx, float* w,
+                 hipStream_t s);
+int launch_permute(const moe_cfg& c, const void* x, const int32_t* idx, int32_t* counts, int32_t* offsets,
+                   int32_t* perm, int32_t* inv, void* Xp, int32_t* chunk_hist, hipStream_t s);
+int launch_pack(const moe_cfg& c, const void* Win, const void* Wgate, const void* Wout, void* packed, hipStream_t s);
+// Runs the FFN of experts [e_first, e_first + e_count); W points at the packed block of e_first and
+// consecutive experts are expert_stride_bytes apart.  max_rows bounds the rows those experts can hold
+// (it sizes the grid; blocks past the real row count exit).
+int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, int e_first, int e_count,
+                      const void* W, size_t expert_stride_bytes, long max_rows, void* H, void* Yp, hipStream_t s);
+int launch_combine(const moe_cfg& c, const void* Yp, const int32_t* inv, const float* w, void* y, hipStream_t s);
+
+}  // namespace moe

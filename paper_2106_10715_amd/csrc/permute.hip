@@ -1,0 +1,139 @@
+// Batching of assignments by expert (CPM-2 Section 6.2: tokens are routed and batched to their
+// experts before computation): a deterministic, stable counting sort of a = t*k + j by expert id,
+// followed by the row gather Xp[row] = x[perm[row] / k].
+//
+//   1. chunk_hist_kernel : LDS histogram of each chunk of kPermChunk assignments
+//   2. scan_kernel       : counts, offsets and, per chunk, the first row of every expert
+//   3. scatter_kernel    : stable rank inside the chunk from wave ballots (no ordered atomics)
+//   4. gather_rows_kernel: 16-byte-vector row copy
+#include "common.h"
+
+namespace moe {
+namespace {
+
+__device__ inline int clamp_expert(int e, int E) { return min(max(e, 0), E - 1); }
+
+__global__ __launch_bounds__(256) void chunk_hist_kernel(const int32_t* __restrict__ idx, int A, int E,
+                                                         int32_t* __restrict__ chunk_hist) {
+    __shared__ int hist[256];
+    hist[threadIdx.x] = 0;
+    __syncthreads();
+    const int a0 = blockIdx.x * kPermChunk;
+    for (int i = threadIdx.x; i < kPermChunk; i += 256) {
+        const int a = a0 + i;
+        if (a < A) atomicAdd(&hist[clamp_expert(idx[a], E)], 1);   // integer counts: order cannot matter
+    }
+    __syncthreads();
+    if (threadIdx.x < E) chunk_hist[static_cast<size_t>(blockIdx.x) * E + threadIdx.x] = hist[threadIdx.x];
+}
+
+// One block; thread e walks the chunks of expert e, turning histograms into running bases.
+__global__ __launch_bounds__(256) void scan_kernel(int32_t* __restrict__ chunk_hist, int chunks, int E,
+                                                   int32_t* __restrict__ counts, int32_t* __restrict__ offsets) {
+    __shared__ int total[256];
+    __shared__ int start[257];
+    const int e = threadIdx.x;
+    int run = 0;
+    if (e < E) {
+        for (int b = 0; b < chunks; ++b) {
+            const size_t at = static_cast<size_t>(b) * E + e;
+            const int h = chunk_hist[at];
+            chunk_hist[at] = run;              // rows of expert e that earlier chunks hold
+            run += h;
+        }
+    }
+    total[e] = e < E ? run : 0;
+    __syncthreads();
+    if (e == 0) {
+        int acc = 0;
+        for (int i = 0; i < E; ++i) { start[i] = acc; acc += total[i]; }
+        start[E] = acc;
+    }
+    __syncthreads();
+    if (e < E) {
+        counts[e] = total[e];
+        offsets[e] = start[e];
+        for (int b = 0; b < chunks; ++b) chunk_hist[static_cast<size_t>(b) * E + e] += start[e];
+    }
+    if (e == 0) offsets[E] = start[E];
+}
+
+__global__ __launch_bounds__(256) void scatter_kernel(const int32_t* __restrict__ idx, int A, int E,
+                                                      const int32_t* __restrict__ chunk_base,
+                                                      int32_t* __restrict__ perm, int32_t* __restrict__ inv) {
+    __shared__ int run[256];          // next free row of each expert for this chunk
+    __shared__ int wcnt[4][256];      // per wave, rows each expert takes in the current round
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    run[threadIdx.x] = threadIdx.x < E ? chunk_base[static_cast<size_t>(blockIdx.x) * E + threadIdx.x] : 0;
+#pragma unroll
+    for (int wv = 0; wv < 4; ++wv) wcnt[wv][threadIdx.x] = 0;
+    __syncthreads();
+    int bits = 0;
+    while ((1 << bits) < E) ++bits;
+    const int a0 = blockIdx.x * kPermChunk;
+    for (int round = 0; round < kPermChunk / 256; ++round) {
+        const int a = a0 + round * 256 + threadIdx.x;
+        const bool valid = a < A;
+        const int e = valid ? clamp_expert(idx[a], E) : 0;
+        // lanes of this wave that hold the same expert
+        unsigned long long peers = __ballot(valid);
+        for (int b = 0; b < bits; ++b) {
+            const bool bit = (e >> b) & 1;
+            const unsigned long long bal = __ballot(bit);
+            peers &= bit ? bal : ~bal;
+        }
+        const int rank = __popcll(peers & ((1ull << lane) - 1ull));
+        if (valid && rank == 0) wcnt[wave][e] = __popcll(peers);
+        __syncthreads();
+        if (valid) {
+            int row = run[e] + rank;
+            for (int wv = 0; wv < wave; ++wv) row += wcnt[wv][e];
+            perm[row] = a;
+            inv[a] = row;
+        }
+        __syncthreads();
+        {
+            const int t = threadIdx.x;
+            run[t] += wcnt[0][t] + wcnt[1][t] + wcnt[2][t] + wcnt[3][t];
+            wcnt[0][t] = 0; wcnt[1][t] = 0; wcnt[2][t] = 0; wcnt[3][t] = 0;
+        }
+        __syncthreads();
+    }
+}
+
+// One block per destination row; 16-byte vectors, coalesced on both sides.
+__global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ perm,
+                                                          int k, int vec_per_row, uint4* __restrict__ Xp) {
+    const int row = blockIdx.x;
+    const int t = perm[row] / k;
+    const uint4* src = x + static_cast<size_t>(t) * vec_per_row;
+    uint4* dst = Xp + static_cast<size_t>(row) * vec_per_row;
+    for (int v = threadIdx.x; v < vec_per_row; v += 256) dst[v] = src[v];
+}
+
+}  // namespace
+
+int launch_permute(const moe_cfg& c, const void* x, const int32_t* idx, int32_t* counts, int32_t* offsets,
+                   int32_t* perm, int32_t* inv, void* Xp, int32_t* chunk_hist, hipStream_t s) {
+    const int A = c.T * c.k;
+    const int chunks = (A + kPermChunk - 1) / kPermChunk;
+    if (chunks > 0) {
+        hipLaunchKernelGGL(chunk_hist_kernel, dim3(chunks), dim3(256), 0, s, idx, A, c.E, chunk_hist);
+        MOE_LAUNCH_CHECK("chunk_hist_kernel");
+    }
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), 0, s, chunk_hist, chunks, c.E, counts, offsets);
+    MOE_LAUNCH_CHECK("scan_kernel");
+    if (chunks > 0) {
+        hipLaunchKernelGGL(scatter_kernel, dim3(chunks), dim3(256), 0, s, idx, A, c.E, chunk_hist, perm, inv);
+        MOE_LAUNCH_CHECK("scatter_kernel");
+        if (Xp != nullptr) {
+            const int vec_per_row = static_cast<int>(c.d * elem_size(c) / 16);
+            hipLaunchKernelGGL(gather_rows_kernel, dim3(A), dim3(256), 0, s, static_cast<const uint4*>(x), perm, c.k,
+                               vec_per_row, static_cast<uint4*>(Xp));
+            MOE_LAUNCH_CHECK("gather_rows_kernel");
+        }
+    }
+    return MOE_OK;
+}
+
+}  // namespace moe

@@ -1,0 +1,93 @@
+"""Host-only checks of the C-ABI library: it loads, exports every entry point the header declares,
+sizes workspaces consistently, and rejects bad arguments before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2106_10715_amd as M
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "moe355.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert {"moe_route", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward"} <= set(names)
+    L = M.lib()
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in moe355.h but not exported"
+
+
+def test_binding_has_the_same_names():
+    for n in ("moe_route", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward", "moe_pack_weights",
+              "moe_workspace_bytes", "moe_expert_bytes"):
+        assert callable(getattr(M, n))
+
+
+def test_sizes():
+    c = M.MoeCfg.make(4096, 4096, 10240, 32)
+    assert M.moe_expert_bytes(c) == 240 * 2 ** 20          # one bf16 expert of the Table 1 shape
+    ws = M.moe_workspace_bytes(c)
+    A = 4096
+    need = A * 10240 * 2 + 2 * A * 4096 * 2 + 4 * A * 4
+    assert need <= ws < need + (1 << 20)
+    c32 = M.MoeCfg.make(64, 256, 512, 4, dtype="f32")
+    assert M.moe_expert_bytes(c32) == 3 * 256 * 512 * 4
+    assert M.moe_workspace_bytes(M.MoeCfg.make(0, 64, 64, 1)) >= 256
+
+
+@pytest.mark.parametrize("kw,frag", [
+    (dict(T=-1, d=64, f=64, E=2), "T must be"),
+    (dict(T=1, d=96, f=64, E=2), "d must be"),
+    (dict(T=1, d=64, f=100, E=2), "f must be"),
+    (dict(T=1, d=64, f=64, E=0), "E must be"),
+    (dict(T=1, d=64, f=64, E=257), "E must be"),
+    (dict(T=1, d=64, f=64, E=4, k=5), "k must be"),
+    (dict(T=1, d=64, f=64, E=16, k=9), "k must be"),
+    (dict(T=1, d=64, f=64, E=2, renorm=2), "renorm"),
+    (dict(T=1, d=64, f=64, E=2, act=3), "act"),
+    (dict(T=1 << 20, d=4096, f=10240, E=2), "2^31"),
+])
+def test_bad_cfg_is_rejected(kw, frag):
+    cfg = M.MoeCfg.make(**kw)
+    with pytest.raises(M.MoeError, match=re.escape(frag)):
+        M.moe_workspace_bytes(cfg)
+    L = M.lib()
+    n = C.c_size_t(0)
+    assert L.moe_expert_bytes(C.byref(cfg), C.byref(n)) == -1
+    assert L.moe_route(C.byref(cfg), None, None, None, None, None, None, None) == -1
+    assert L.moe_layer_forward(C.byref(cfg), None, None, None, None, None, None, None, None) == -1
+    assert frag.encode() in L.moe_last_error()
+
+
+def test_null_pointers_are_rejected_before_launch():
+    L = M.lib()
+    cfg = M.MoeCfg.make(8, 64, 64, 2)
+    assert L.moe_route(None, None, None, None, None, None, None, None) == -1
+    assert L.moe_route(C.byref(cfg), None, None, None, None, None, None, None) == -1
+    assert b"W_g is NULL" in L.moe_last_error()
+    assert L.moe_permute(C.byref(cfg), None, None, None, None, None, None, None, None, None) == -1
+    assert L.moe_expert_ffn(C.byref(cfg), None, None, None, None, None, None) == -1
+    assert L.moe_combine(C.byref(cfg), None, None, None, None, None) == -1
+    assert L.moe_layer_forward(C.byref(cfg), None, None, None, None, None, None, None, None) == -1
+    h = C.c_void_p(None)
+    assert L.moe_stream_ctx_create(C.byref(cfg), None, 0, None, 2, C.byref(h)) == -1
+    assert L.moe_stream_ctx_destroy(None) == 0
+    # misaligned buffers
+    buf = C.create_string_buffer(4096)
+    base = C.addressof(buf)
+    al = (base + 255) & ~255
+    assert L.moe_combine(C.byref(cfg), C.c_void_p(al + 2), C.c_void_p(al), C.c_void_p(al), C.c_void_p(al), None) == -1
+    assert b"aligned" in L.moe_last_error()
+    # wrong expert size / slot count for the streamed mode
+    assert L.moe_stream_ctx_create(C.byref(cfg), C.c_void_p(al), 123, C.c_void_p(al), 2, C.byref(h)) == -1
+    assert b"expert_bytes" in L.moe_last_error()
+    assert L.moe_stream_ctx_create(C.byref(cfg), C.c_void_p(al), 3 * 64 * 64 * 2, C.c_void_p(al), 0, C.byref(h)) == -1
+    assert b"K must be" in L.moe_last_error()

@@ -1,0 +1,130 @@
+"""GPU parity of the whole layer (resident and host-streamed) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import moe_workloads as W
+import paper_2106_10715_amd as M
+from oracle import moe_oracle as O
+from paper_2106_10715_amd import harness as H
+
+pytestmark = pytest.mark.gpu
+TOL = {"f32": 1e-5, "bf16": 1e-2}
+
+
+def rel_l2(got, ref):
+    den = np.linalg.norm(ref)
+    return float(np.linalg.norm(np.asarray(got, np.float64) - ref) / (den if den > 0 else 1.0))
+
+
+def oracle_layer(wl, act=0):
+    x = W.gen_x(wl)
+    Wg, bias = W.gen_gate(wl)
+    return O.layer_forward(x, Wg, lambda e: W.gen_expert(wl, e), wl.E, wl.k, bias, wl.renorm, act)
+
+
+def stagewise(L):
+    """The layer as five separate C-ABI calls; returns every intermediate."""
+    cfg, A = L.cfg, L.wl.T * L.wl.k
+    dev = "cuda"
+    idx = torch.empty((L.wl.T, cfg.k), dtype=torch.int32, device=dev)
+    w = torch.empty((L.wl.T, cfg.k), dtype=torch.float32, device=dev)
+    counts = torch.empty(cfg.E, dtype=torch.int32, device=dev)
+    offsets = torch.empty(cfg.E + 1, dtype=torch.int32, device=dev)
+    perm = torch.empty(A, dtype=torch.int32, device=dev)
+    inv = torch.empty(A, dtype=torch.int32, device=dev)
+    Xp = torch.empty((A, cfg.d), dtype=cfg.torch_dtype, device=dev)
+    Yp = torch.empty((A, cfg.d), dtype=cfg.torch_dtype, device=dev)
+    y = torch.empty((L.wl.T, cfg.d), dtype=cfg.torch_dtype, device=dev)
+    M.moe_route(cfg, L.x, L.Wg, L.bias, idx, w, L.ws)
+    M.moe_permute(cfg, L.x, idx, counts, offsets, perm, inv, Xp, L.ws)
+    M.moe_expert_ffn(cfg, Xp, offsets, L.packed, Yp, L.ws)
+    M.moe_combine(cfg, Yp, inv, w, y)
+    torch.cuda.synchronize()
+    return dict(idx=idx, w=w, counts=counts, offsets=offsets, perm=perm, inv=inv, Xp=Xp, Yp=Yp, y=y)
+
+
+MID = [
+    W.CONFIGS["c1"],
+    W.Workload("mid-bf16-top1", T=700, d=256, f=384, E=6, k=1, dtype="bf16", seed=21),
+    W.Workload("mid-bf16-top2-zipf", T=900, d=192, f=320, E=12, k=2, dtype="bf16", seed=22, zipf_s=1.2, n_dead=3),
+    W.Workload("mid-f32-top3-full", T=150, d=128, f=256, E=5, k=3, dtype="f32", seed=23, renorm=0),
+    W.Workload("one-expert", T=130, d=128, f=128, E=1, k=1, dtype="bf16", seed=24),
+]
+
+
+@pytest.mark.parametrize("wl", MID, ids=lambda w: w.name)
+def test_layer_forward_resident_matches_oracle(wl):
+    L = H.build_layer(wl)
+    M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)
+    torch.cuda.synchronize()
+    y_ref, r, p, Yp_ref = oracle_layer(wl)
+    got = H.to_f64(L.y)
+    assert np.isfinite(got).all()
+    assert rel_l2(got, y_ref) <= TOL[wl.dtype]
+    s = stagewise(L)
+    assert np.array_equal(s["idx"].cpu().numpy(), r.idx)
+    assert np.array_equal(s["counts"].cpu().numpy(), p.counts)
+    assert np.array_equal(s["offsets"].cpu().numpy(), p.offsets)
+    assert np.array_equal(s["perm"].cpu().numpy(), p.perm)
+    assert np.array_equal(s["inv"].cpu().numpy(), p.inv)
+    assert rel_l2(s["w"].cpu().numpy(), r.w) <= 1e-5
+    assert rel_l2(H.to_f64(s["Yp"]), Yp_ref) <= TOL[wl.dtype]
+    assert torch.equal(s["y"], L.y)                      # the fused entry point runs the same kernels
+    if wl.n_dead:
+        assert (p.counts == 0).sum() >= wl.n_dead
+
+
+def test_identical_experts_give_the_dense_ffn():
+    # Section 2.3: the MoE model is initialised with copies of the dense FFN
+    wl = W.Workload("dup", T=300, d=128, f=256, E=4, k=2, dtype="bf16", seed=31)
+    one = W.gen_expert(wl, 0)
+    L = H.build_layer(wl, experts=lambda e: one)
+    M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)
+    torch.cuda.synchronize()
+    dense = O.expert_ffn_rows(W.gen_x(wl), *one)
+    assert rel_l2(H.to_f64(L.y), dense) <= 1e-2
+
+
+def test_zero_tokens_is_a_no_op():
+    wl = W.Workload("empty", T=0, d=64, f=64, E=2, k=1, dtype="bf16", seed=1)
+    cfg = H.cfg_of(wl)
+    ws = torch.empty(M.moe_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+    z = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    Wg = torch.zeros((64, 2), dtype=torch.bfloat16, device="cuda")
+    packed = torch.zeros((2, M.moe_expert_bytes(cfg)), dtype=torch.uint8, device="cuda")
+    M.moe_layer_forward(cfg, z, Wg, None, packed, None, z, ws)
+    counts = torch.full((2,), 5, dtype=torch.int32, device="cuda")
+    offsets = torch.full((3,), 5, dtype=torch.int32, device="cuda")
+    e = torch.empty(0, dtype=torch.int32, device="cuda")
+    M.moe_permute(cfg, z, e, counts, offsets, e, e, z, ws)
+    torch.cuda.synchronize()
+    assert counts.tolist() == [0, 0] and offsets.tolist() == [0, 0, 0]
+
+
+@pytest.mark.parametrize("wl", [
+    W.Workload("str-top1", T=600, d=256, f=384, E=6, k=1, dtype="bf16", seed=41),
+    W.Workload("str-top2-dead", T=500, d=192, f=320, E=9, k=2, dtype="bf16", seed=42, zipf_s=1.2, n_dead=3),
+    W.Workload("str-f32", T=64, d=256, f=512, E=4, k=1, dtype="f32", seed=43),
+], ids=lambda w: w.name)
+@pytest.mark.parametrize("K", [1, 2, 3])
+def test_streamed_equals_resident_bitwise(wl, K):
+    L = H.build_layer(wl, host_copy=True)
+    M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)
+    torch.cuda.synchronize()
+    y_res = L.y.clone()
+    eb = M.moe_expert_bytes(L.cfg)
+    slots = torch.empty((K, eb), dtype=torch.uint8, device="cuda")
+    ctx = M.StreamCtx(L.cfg, L.host_packed, slots, K)
+    for rep in range(3):                                  # slots are reused across calls
+        L.y.fill_(float("nan"))
+        M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, None, ctx, L.y, L.ws)
+        torch.cuda.synchronize()
+        assert torch.equal(L.y, y_res), f"rep {rep}"
+    st = ctx.stats()
+    _, r, p, _ = oracle_layer(wl)
+    assert st["n_loaded"] == int((p.counts > 0).sum())     # empty experts are never loaded
+    assert st["bytes"] == st["n_loaded"] * eb
+    ctx.close()
+    y_ref = oracle_layer(wl)[0]
+    assert rel_l2(H.to_f64(y_res), y_ref) <= TOL[wl.dtype]

@@ -1,0 +1,284 @@
+"""GPU parity of every stage of the layer against the CPU oracle, called through the C ABI.
+
+Bars: routing indices, counts, offsets and permutation bit-exact; fp32 outputs within 1e-5 and
+bf16 outputs within 1e-2 normalised L2 of the fp64 oracle evaluated on the same stored inputs."""
+import numpy as np
+import pytest
+import torch
+
+import moe_workloads as W
+import paper_2106_10715_amd as M
+from oracle import moe_oracle as O
+from paper_2106_10715_amd import harness as H
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 1e-2}
+
+
+def rel_l2(got, ref):
+    ref = np.asarray(ref, dtype=np.float64)
+    den = np.linalg.norm(ref)
+    return float(np.linalg.norm(np.asarray(got, dtype=np.float64) - ref) / (den if den > 0 else 1.0))
+
+
+def rounded(a, dtype):
+    a = np.ascontiguousarray(a, dtype=np.float32).copy()
+    return W.round_to_bf16(a) if dtype == "bf16" else a
+
+
+def make_inputs(seed, T, d, E, dtype, bias=False):
+    rng = np.random.default_rng(seed)
+    x = rounded(rng.standard_normal((T, d)), dtype)
+    Wg = rounded(rng.standard_normal((d, E)) / np.sqrt(d), dtype)
+    b = rng.standard_normal(E).astype(np.float32) * 0.5 if bias else None
+    return x, Wg, b
+
+
+def gpu_route(cfg, x, Wg, b, dtype):
+    T, k = cfg.T, cfg.k
+    dx, dW = H.to_device(x, dtype), H.to_device(Wg, dtype)
+    db = torch.from_numpy(b).cuda() if b is not None else None
+    idx = torch.full((T, k), -7, dtype=torch.int32, device="cuda")
+    w = torch.full((T, k), -7.0, dtype=torch.float32, device="cuda")
+    ws = torch.empty(M.moe_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+    M.moe_route(cfg, dx, dW, db, idx, w, ws)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), w.cpu().numpy()
+
+
+# ------------------------------------------------------------------------------------------- route
+
+ROUTE_CASES = [
+    # T, d, E, k, dtype, renorm, bias
+    (64, 256, 4, 1, "f32", 1, False),          # the tiny fp32 configuration's gate
+    (1, 64, 1, 1, "bf16", 1, False),
+    (63, 128, 8, 2, "bf16", 1, True),
+    (257, 512, 32, 1, "bf16", 1, False),
+    (130, 192, 33, 3, "bf16", 0, True),
+    (100, 256, 64, 2, "bf16", 1, True),
+    (77, 128, 100, 8, "f32", 0, False),
+    (50, 64, 256, 4, "bf16", 1, True),
+    (33, 4096, 32, 1, "bf16", 1, False),       # the paper's width
+    (19, 320, 8, 8, "f32", 1, True),           # k = E
+]
+
+
+@pytest.mark.parametrize("T,d,E,k,dtype,renorm,bias", ROUTE_CASES)
+def test_route_matches_oracle(T, d, E, k, dtype, renorm, bias):
+    x, Wg, b = make_inputs(100 + T + E, T, d, E, dtype, bias)
+    cfg = M.MoeCfg.make(T, d, 64, E, k, dtype, renorm)
+    idx, w = gpu_route(cfg, x, Wg, b, dtype)
+    ref = O.route(x, Wg, k, b, renorm)
+    assert np.array_equal(idx, ref.idx), f"min oracle margin {ref.margin.min():.3e}"
+    assert rel_l2(w, ref.w) <= 1e-5
+    assert np.abs(w - ref.w).max() <= 2e-5
+    if renorm and k == 1:
+        assert np.all(w == 1.0)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_route_ties_and_near_ties(dtype):
+    T, d, E, k = 96, 256, 12, 3
+    x, Wg, _ = make_inputs(5, T, d, E, dtype)
+    Wg[:, 7] = Wg[:, 2]                      # exact ties between experts 2, 7, 9
+    Wg[:, 9] = Wg[:, 2]
+    x[10] = 0.0                              # all logits exactly 0
+    x[11] = 0.0
+    # near ties that fp32 accumulation cannot resolve: expert 5 = expert 4 except one tiny coordinate
+    Wg[:, 5] = Wg[:, 4]
+    Wg[3, 5] = rounded(np.array([Wg[3, 4] * (1 + 2.0 ** -7)]), dtype)[0]
+    cfg = M.MoeCfg.make(T, d, 64, E, k, dtype)
+    idx, w = gpu_route(cfg, x, Wg, None, dtype)
+    ref = O.route(x, Wg, k)
+    assert np.array_equal(idx, ref.idx)
+    assert idx[10].tolist() == [0, 1, 2] and idx[11].tolist() == [0, 1, 2]
+    assert rel_l2(w, ref.w) <= 1e-5
+    # the case is only meaningful if some decisions really were inside fp32 noise
+    assert (ref.margin < 1e-6).sum() >= 2
+
+
+def test_route_dead_experts_get_nothing():
+    T, d, E, k = 200, 128, 16, 2
+    x, Wg, _ = make_inputs(6, T, d, E, "bf16")
+    b = np.zeros(E, dtype=np.float32)
+    b[[3, 8, 15]] = W.DEAD_BIAS
+    cfg = M.MoeCfg.make(T, d, 64, E, k, "bf16")
+    idx, w = gpu_route(cfg, x, Wg, b, "bf16")
+    ref = O.route(x, Wg, k, b)
+    assert np.array_equal(idx, ref.idx)
+    assert not np.isin(idx, [3, 8, 15]).any()
+    np.testing.assert_allclose(w.sum(axis=1), 1.0, atol=3e-7)
+
+
+# ------------------------------------------------------------------------------------------- permute
+
+def gpu_permute(cfg, x, idx_np, dtype, with_rows=True):
+    A = cfg.T * cfg.k
+    dx = H.to_device(x, dtype)
+    didx = torch.from_numpy(np.ascontiguousarray(idx_np, dtype=np.int32)).cuda()
+    counts = torch.full((cfg.E,), -1, dtype=torch.int32, device="cuda")
+    offsets = torch.full((cfg.E + 1,), -1, dtype=torch.int32, device="cuda")
+    perm = torch.full((A,), -1, dtype=torch.int32, device="cuda")
+    inv = torch.full((A,), -1, dtype=torch.int32, device="cuda")
+    Xp = torch.zeros((A, cfg.d), dtype=cfg.torch_dtype, device="cuda") if with_rows else None
+    ws = torch.empty(M.moe_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+    M.moe_permute(cfg, dx, didx, counts, offsets, perm, inv, Xp, ws)
+    torch.cuda.synchronize()
+    return counts.cpu().numpy(), offsets.cpu().numpy(), perm.cpu().numpy(), inv.cpu().numpy(), Xp
+
+
+@pytest.mark.parametrize("T,d,E,k,dtype,skew", [
+    (64, 256, 4, 1, "f32", 0.0),
+    (1, 64, 1, 1, "bf16", 0.0),
+    (1025, 64, 7, 1, "bf16", 0.0),           # crosses a chunk boundary by one
+    (3000, 128, 32, 2, "bf16", 1.2),         # several chunks, ragged tail, skewed
+    (2048, 64, 256, 4, "bf16", 0.0),
+    (5000, 64, 64, 2, "f32", 2.0),           # heavy skew, some experts empty
+    (999, 192, 3, 3, "bf16", 0.0),           # k = E
+])
+def test_permute_matches_oracle(T, d, E, k, dtype, skew):
+    rng = np.random.default_rng(T + E)
+    x = rounded(rng.standard_normal((T, d)), dtype)
+    p = (np.arange(1, E + 1) ** -skew) if skew else np.ones(E)
+    p = p / p.sum()
+    idx = np.stack([rng.choice(E, size=k, replace=False, p=p) for _ in range(T)]).astype(np.int32)
+    cfg = M.MoeCfg.make(T, d, 64, E, k, dtype)
+    counts, offsets, perm, inv, Xp = gpu_permute(cfg, x, idx, dtype)
+    ref = O.permute(x, idx, E)
+    assert np.array_equal(counts, ref.counts)
+    assert np.array_equal(offsets, ref.offsets)
+    assert np.array_equal(perm, ref.perm)
+    assert np.array_equal(inv, ref.inv)
+    assert np.array_equal(H.to_f64(Xp), ref.Xp)       # pure data movement: exact
+
+
+def test_permute_is_deterministic_and_index_only_mode():
+    T, d, E, k = 4100, 64, 16, 2
+    rng = np.random.default_rng(1)
+    x = rounded(rng.standard_normal((T, d)), "bf16")
+    idx = np.stack([rng.choice(E, size=k, replace=False) for _ in range(T)]).astype(np.int32)
+    cfg = M.MoeCfg.make(T, d, 64, E, k, "bf16")
+    a = gpu_permute(cfg, x, idx, "bf16")
+    b = gpu_permute(cfg, x, idx, "bf16", with_rows=False)
+    for u, v in zip(a[:4], b[:4]):
+        assert np.array_equal(u, v)
+
+
+def test_permute_all_tokens_to_one_expert():
+    T, d, E = 2500, 64, 9
+    x = rounded(np.random.default_rng(2).standard_normal((T, d)), "bf16")
+    idx = np.full((T, 1), 4, dtype=np.int32)
+    cfg = M.MoeCfg.make(T, d, 64, E, 1, "bf16")
+    counts, offsets, perm, inv, Xp = gpu_permute(cfg, x, idx, "bf16")
+    assert counts.tolist() == [0, 0, 0, 0, T, 0, 0, 0, 0]
+    assert np.array_equal(perm, np.arange(T)) and np.array_equal(inv, np.arange(T))
+    assert offsets.tolist() == [0] * 5 + [T] * 5
+
+
+# ------------------------------------------------------------------------------------------- pack
+
+def packed_reference(W_in, W_gate, W_out):
+    """The packed bf16 layout as the header defines it, written out with plain loops over fragments."""
+    d, f = W_in.shape
+    out = []
+
+    def frag(Wm, s, col0):
+        fr = np.empty(512, dtype=np.uint16)
+        for l in range(64):
+            for j in range(8):
+                fr[8 * l + j] = Wm[16 * s + 8 * (l // 32) + j, col0 + l % 32]
+        return fr
+    gate, win, wout = W.bf16_bits(W_gate), W.bf16_bits(W_in), W.bf16_bits(W_out)
+    for n in range(f // 32):
+        for s in range(d // 16):
+            out.append(frag(gate, s, 32 * n))
+            out.append(frag(win, s, 32 * n))
+    for p in range(d // 64):
+        for s in range(f // 16):
+            out.append(frag(wout, s, 64 * p))
+            out.append(frag(wout, s, 64 * p + 32))
+    return np.concatenate(out)
+
+
+def test_pack_layout_bf16_and_f32():
+    d, f = 128, 192
+    rng = np.random.default_rng(3)
+    mats = [rounded(rng.standard_normal(s), "bf16") for s in ((d, f), (d, f), (f, d))]
+    cfg = M.MoeCfg.make(1, d, f, 1, 1, "bf16")
+    dev = [H.to_device(m, "bf16") for m in mats]
+    out = torch.zeros(M.moe_expert_bytes(cfg), dtype=torch.uint8, device="cuda")
+    M.moe_pack_weights(cfg, dev[0], dev[1], dev[2], out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, packed_reference(*mats))
+    cfg32 = M.MoeCfg.make(1, d, f, 1, 1, "f32")
+    dev32 = [H.to_device(m, "f32") for m in mats]
+    out32 = torch.zeros(M.moe_expert_bytes(cfg32), dtype=torch.uint8, device="cuda")
+    M.moe_pack_weights(cfg32, dev32[0], dev32[1], dev32[2], out32)
+    torch.cuda.synchronize()
+    got32 = out32.cpu().numpy().view(np.float32)
+    assert np.array_equal(got32, np.concatenate([mats[1].ravel(), mats[0].ravel(), mats[2].ravel()]))
+
+
+# ------------------------------------------------------------------------------------------- expert FFN
+
+def run_ffn(T, d, f, E, k, dtype, counts, act=0, seed=0):
+    """Rows already batched by expert with the given counts; returns (gpu Yp, oracle Yp)."""
+    A = int(np.sum(counts))
+    assert A == T * k
+    rng = np.random.default_rng(seed)
+    Xp = rounded(rng.standard_normal((A, d)), dtype)
+    ex = [(rounded(rng.standard_normal((d, f)) * 0.05, dtype), rounded(rng.standard_normal((d, f)) * 0.05, dtype),
+           rounded(rng.standard_normal((f, d)) * 0.05, dtype)) for _ in range(E)]
+    offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    cfg = M.MoeCfg.make(T, d, f, E, k, dtype, 1, act)
+    wl = W.Workload("t", T, d, f, E, k, dtype, 0)
+    packed, _ = H.pack_experts(wl, cfg, experts=lambda e: ex[e])
+    dXp = H.to_device(Xp, dtype)
+    doff = torch.from_numpy(offsets).cuda()
+    Yp = torch.full((A, d), float("nan"), dtype=cfg.torch_dtype, device="cuda")
+    ws = torch.empty(M.moe_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+    M.moe_expert_ffn(cfg, dXp, doff, packed, Yp, ws)
+    torch.cuda.synchronize()
+    ref = O.expert_ffn(Xp.astype(np.float64), offsets, lambda e: ex[e], act)
+    return H.to_f64(Yp), ref, offsets
+
+
+@pytest.mark.parametrize("d,f,E,counts,dtype,act", [
+    (256, 512, 4, [20, 0, 37, 7], "f32", 0),                 # fp32 path, an empty expert
+    (128, 192, 5, [130, 0, 1, 300, 69], "bf16", 0),          # several row tiles, ragged tails, empty expert
+    (64, 64, 3, [1, 1, 1], "bf16", 0),                       # smallest legal shape: idle waves in the block
+    (192, 320, 2, [129, 127], "bf16", 1),                    # tanh GELU
+    (320, 128, 6, [0, 0, 64, 0, 0, 200], "f32", 1),
+    (512, 1024, 3, [257, 128, 31], "bf16", 0),
+])
+def test_expert_ffn_matches_oracle(d, f, E, counts, dtype, act):
+    A = sum(counts)
+    got, ref, offsets = run_ffn(A, d, f, E, 1, dtype, counts, act, seed=d + f)
+    assert np.isfinite(got).all()
+    assert rel_l2(got, ref) <= TOL[dtype]
+    for e in range(E):                                        # per segment, so a bad small expert cannot hide
+        lo, hi = offsets[e], offsets[e + 1]
+        if hi > lo:
+            assert rel_l2(got[lo:hi], ref[lo:hi]) <= TOL[dtype], f"expert {e}"
+
+
+# ------------------------------------------------------------------------------------------- combine
+
+@pytest.mark.parametrize("T,d,k,dtype", [(64, 256, 1, "f32"), (301, 128, 2, "bf16"), (77, 192, 8, "bf16"),
+                                         (50, 64, 3, "f32")])
+def test_combine_matches_oracle(T, d, k, dtype):
+    rng = np.random.default_rng(T)
+    A = T * k
+    Yp = rounded(rng.standard_normal((A, d)), dtype)
+    inv = rng.permutation(A).astype(np.int32)
+    w = rng.random((T, k)).astype(np.float32)
+    w /= w.sum(axis=1, keepdims=True)
+    cfg = M.MoeCfg.make(T, d, 64, 8, k, dtype)
+    y = torch.empty((T, d), dtype=cfg.torch_dtype, device="cuda")
+    M.moe_combine(cfg, H.to_device(Yp, dtype), torch.from_numpy(inv).cuda(), torch.from_numpy(w).cuda(), y)
+    torch.cuda.synchronize()
+    ref = O.combine(Yp.astype(np.float64), inv, w)
+    got = H.to_f64(y)
+    assert rel_l2(got, ref) <= (1e-6 if dtype == "f32" else 4e-3)     # one rounding to storage
