@@ -83,21 +83,50 @@ def gate_logits(x: np.ndarray, Wg: np.ndarray, bias: Optional[np.ndarray] = None
     return L
 
 
+def exact_logits_row(xt: np.ndarray, Wg: np.ndarray, bias: Optional[np.ndarray] = None) -> np.ndarray:
+    """One token's logits as correctly rounded exact sums (math.fsum over the products, which are
+    exact in fp64 for bf16/fp32 stored inputs): independent of summation order, so identical gate
+    columns give identical logits and "tie" means a tie in exact arithmetic."""
+    xt = np.asarray(xt, dtype=np.float64)
+    Wg = np.asarray(Wg, dtype=np.float64)
+    out = np.empty(Wg.shape[1], dtype=np.float64)
+    for e in range(Wg.shape[1]):
+        terms = (xt * Wg[:, e]).tolist()
+        if bias is not None:
+            terms.append(float(bias[e]))
+        out[e] = math.fsum(terms)
+    return out
+
+
+def _ranked(L: np.ndarray, k: int):
+    order = np.argsort(-L, axis=1, kind="stable")   # descending logit, equal logits keep ascending expert index
+    top = np.take_along_axis(L, order[:, :min(k + 1, L.shape[1])], axis=1)
+    gaps = top[:, :-1] - top[:, 1:] if top.shape[1] > 1 else np.full((L.shape[0], 1), np.inf)
+    return order, top, gaps.min(axis=1)
+
+
 def route(x: np.ndarray, Wg: np.ndarray, k: int = 1, bias: Optional[np.ndarray] = None,
           renorm: int = 1) -> Routing:
-    """Gate each token to its k best experts (Section 2.1: one expert per token, k = 1)."""
-    L = gate_logits(x, Wg, bias)
+    """Gate each token to its k best experts (Section 2.1: one expert per token, k = 1).
+
+    The ranking is the one exact arithmetic gives.  The matrix product is a library matmul whose
+    rounding error is at most about d * 2^-53 * |x_t| * |W_g column|; any token whose k+1 best
+    logits are not separated by more than that bound is re-evaluated with exact_logits_row.
+    """
+    x64 = np.asarray(x, dtype=np.float64)
+    W64 = np.asarray(Wg, dtype=np.float64)
+    L = gate_logits(x64, W64, bias)
     T, E = L.shape
     if not 1 <= k <= E:
         raise ValueError("need 1 <= k <= E")
-    # stable sort of -L: descending logit, equal logits keep ascending expert index
-    order = np.argsort(-L, axis=1, kind="stable")
+    order, top, margin = _ranked(L, k)
+    d = x64.shape[1]
+    col = np.sqrt((W64 * W64).sum(axis=0)).max() if E else 0.0
+    bound = (d + 4) * 2.0 ** -53 * (np.sqrt((x64 * x64).sum(axis=1)) * col + np.abs(top).max(axis=1))
+    for t in np.nonzero(margin <= 4.0 * bound)[0]:
+        L[t] = exact_logits_row(x64[t], W64, bias)
+    order, top, margin = _ranked(L, k)
     idx = order[:, :k].astype(np.int32)
-    top = np.take_along_axis(L, order[:, :min(k + 1, E)], axis=1)
-    if top.shape[1] > 1:
-        margin = (top[:, :-1] - top[:, 1:]).min(axis=1)
-    else:
-        margin = np.full(T, np.inf)
     sel = top[:, :k]
     if renorm:
         ex = np.exp(sel - sel[:, :1])

@@ -128,6 +128,27 @@ def test_crafted_ties_go_to_lowest_index():
     assert np.all(y[2] == 0.0)     # FFN(0) = 0: no biases anywhere
 
 
+def test_duplicate_gate_columns_tie_exactly_for_fp32_inputs():
+    # a library matmul may round identical columns differently; ties are defined in exact arithmetic
+    rng = np.random.default_rng(5)
+    T, d, E, k = 96, 256, 12, 3
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    Wg = (rng.standard_normal((d, E)) / 16).astype(np.float32)
+    Wg[:, 7] = Wg[:, 2]
+    Wg[:, 9] = Wg[:, 2]
+    r = O.route(x, Wg, k=k)
+    _, idxb, _ = B.moe_layer(x[:, :].astype(np.float64).tolist(), Wg.astype(np.float64).tolist(),
+                             [([[0.0]] * d, [[0.0]] * d, [[0.0] * d])] * E, k=k)
+    assert r.idx.tolist() == idxb                      # brute force sums with math.fsum: exact too
+    for row in r.idx.tolist():
+        for a, b in ((2, 7), (7, 9), (2, 9)):
+            if b in row:
+                assert a in row and row.index(a) < row.index(b)
+    e = O.exact_logits_row(x[0], Wg)
+    assert e[2] == e[7] == e[9]
+    np.testing.assert_allclose(e, x[0].astype(np.float64) @ Wg.astype(np.float64), rtol=0, atol=1e-12)
+
+
 # ---------------------------------------------------------------- dense special cases (another library)
 
 def _torch_dense_ffn(x, W_in, W_gate, W_out):
