@@ -157,6 +157,19 @@ int moe_stream_ctx_destroy(moe_stream_ctx* sctx);
  */
 int moe_stream_ctx_stats(moe_stream_ctx* sctx, int32_t* n_loaded, size_t* bytes, float* copy_ms);
 
+/*
+ * Measurement aid: per-stage timing of resident moe_layer_forward calls.  After
+ * moe_stage_timing_enable(max_calls) each of the next max_calls resident calls records hipEvents on
+ * its stream around its five stages (route, permute, expert up-projection kernel, expert
+ * down-projection kernel, combine; Sections 2.1 and 6.2 name the stages).  moe_stage_timing_read waits
+ * for the recorded calls and writes ms[call][5] (host, row-major, at most capacity_calls rows);
+ * n_calls receives the number of calls recorded.  Process-wide state, not thread-safe; events are the
+ * only resources held and moe_stage_timing_disable releases them.
+ */
+int moe_stage_timing_enable(int32_t max_calls);
+int moe_stage_timing_read(float* ms, int32_t capacity_calls, int32_t* n_calls);
+int moe_stage_timing_disable(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -7,5 +7,5 @@ the shared library and raises if it has not been built (there is no fallback pat
 from .binding import (  # noqa: F401
     MOE_BF16, MOE_F32, MoeCfg, MoeError, StreamCtx, lib, lib_path,
     moe_combine, moe_expert_bytes, moe_expert_ffn, moe_layer_forward, moe_pack_weights, moe_permute,
-    moe_route, moe_workspace_bytes,
+    moe_route, moe_workspace_bytes, moe_stage_timing_enable, moe_stage_timing_read, moe_stage_timing_disable, STAGES,
 )

@@ -58,6 +58,9 @@ def lib() -> C.CDLL:
             "moe_stream_ctx_create": [cfgp, p, C.c_size_t, p, C.c_int32, C.POINTER(C.c_void_p)],
             "moe_stream_ctx_destroy": [p],
             "moe_stream_ctx_stats": [p, C.POINTER(C.c_int32), C.POINTER(C.c_size_t), C.POINTER(C.c_float)],
+            "moe_stage_timing_enable": [C.c_int32],
+            "moe_stage_timing_read": [C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)],
+            "moe_stage_timing_disable": [],
         }
         for name, args in sigs.items():
             fn = getattr(L, name)
@@ -156,3 +159,23 @@ class StreamCtx:
 def moe_layer_forward(cfg, x, W_g, gate_bias, W_packed, sctx: Optional[StreamCtx], y, ws, stream=None) -> None:
     _check(lib().moe_layer_forward(C.byref(cfg), _ptr(x), _ptr(W_g), _ptr(gate_bias), _ptr(W_packed),
                                    sctx.handle if sctx is not None else None, _ptr(y), _ptr(ws), _stream(stream)))
+
+
+STAGES = ("route", "permute", "ffn_up", "ffn_down", "combine")
+
+
+def moe_stage_timing_enable(max_calls: int) -> None:
+    _check(lib().moe_stage_timing_enable(max_calls))
+
+
+def moe_stage_timing_read(max_calls: int):
+    """List of per-call dicts {stage: ms}."""
+    buf = (C.c_float * (max_calls * len(STAGES)))()
+    n = C.c_int32(0)
+    _check(lib().moe_stage_timing_read(buf, max_calls, C.byref(n)))
+    got = min(n.value, max_calls)
+    return [{s: buf[c * len(STAGES) + i] for i, s in enumerate(STAGES)} for c in range(got)]
+
+
+def moe_stage_timing_disable() -> None:
+    _check(lib().moe_stage_timing_disable())

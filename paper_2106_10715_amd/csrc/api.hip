@@ -80,6 +80,16 @@ struct moe_stream_ctx {
     int n_loaded;
 };
 
+// Optional per-stage event timing of resident moe_layer_forward calls (measurement aid).
+namespace {
+constexpr int kStageEvents = 6;   // before route, after route, permute, up, down, combine
+struct StageTimer {
+    bool on = false;
+    int cap = 0, n = 0;
+    hipEvent_t* ev = nullptr;
+} g_timer;
+}  // namespace
+
 #define REQUIRE(ptr, name) \
     if ((ptr) == nullptr) return fail(MOE_ERR_INVALID_ARG, "%s is NULL", name)
 #define REQUIRE_ALIGNED(ptr, name) \
@@ -162,7 +172,7 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
     if (int rc = check_cfg(cfg)) return rc;
     REQUIRE(W_g, "W_g");
     if (sctx == nullptr) { REQUIRE(W_packed, "W_packed (resident mode)"); REQUIRE_ALIGNED(W_packed, "W_packed"); }
-    if (sctx != nullptr && memcmp(&sctx->cfg, cfg, sizeof(int32_t) * 2) != 0 &&
+    if (sctx != nullptr &&
         (sctx->cfg.d != cfg->d || sctx->cfg.f != cfg->f || sctx->cfg.E != cfg->E || sctx->cfg.dtype != cfg->dtype))
         return fail(MOE_ERR_INVALID_ARG, "stream context was created for another d/f/E/dtype");
     if (cfg->T == 0) return MOE_OK;
@@ -184,14 +194,21 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
     size_t eb = 0;
     moe_expert_bytes(cfg, &eb);
 
+    hipEvent_t* tev = nullptr;     // this call's stage events, if stage timing is on and has room
+    if (sctx == nullptr && g_timer.on && g_timer.n < g_timer.cap) tev = g_timer.ev + kStageEvents * g_timer.n++;
+    if (tev) MOE_HIP_CHECK(hipEventRecord(tev[0], s));
     if (int rc = launch_route(c, x, W_g, gate_bias, idx, w, s)) return rc;
+    if (tev) MOE_HIP_CHECK(hipEventRecord(tev[1], s));
     if (int rc = launch_permute(c, x, idx, counts, offsets, perm, inv, base + L.Xp,
                                 reinterpret_cast<int32_t*>(base + L.chunk_hist), s))
         return rc;
+    if (tev) MOE_HIP_CHECK(hipEventRecord(tev[2], s));
 
     if (sctx == nullptr) {
-        if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, 0, c.E, W_packed, eb, A, base + L.H, base + L.Yp, s))
+        if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, 0, c.E, W_packed, eb, A, base + L.H, base + L.Yp, s,
+                                       tev ? tev[3] : nullptr))
             return rc;
+        if (tev) MOE_HIP_CHECK(hipEventRecord(tev[4], s));
     } else {
         // The host has to know which experts hold tokens (and how many) before it can queue loads.
         MOE_HIP_CHECK(hipMemcpyAsync(sctx->h_counts, counts, sizeof(int32_t) * c.E, hipMemcpyDeviceToHost, s));
@@ -219,7 +236,52 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
         sctx->n_loaded = i;
         sctx->timed = i > 0;
     }
-    return launch_combine(c, base + L.Yp, inv, w, y, s);
+    if (int rc = launch_combine(c, base + L.Yp, inv, w, y, s)) return rc;
+    if (tev) MOE_HIP_CHECK(hipEventRecord(tev[5], s));
+    return MOE_OK;
+}
+
+int moe_stage_timing_enable(int32_t max_calls) {
+    if (max_calls < 1 || max_calls > 4096) return fail(MOE_ERR_INVALID_ARG, "max_calls must be in [1, 4096]");
+    moe_stage_timing_disable();
+    g_timer.ev = new (std::nothrow) hipEvent_t[static_cast<size_t>(max_calls) * kStageEvents]();
+    if (g_timer.ev == nullptr) return fail(MOE_ERR_HIP, "out of host memory");
+    g_timer.cap = max_calls;
+    for (int i = 0; i < max_calls * kStageEvents; ++i) {
+        const hipError_t e = hipEventCreate(&g_timer.ev[i]);
+        if (e != hipSuccess) {
+            g_timer.cap = i / kStageEvents;
+            moe_stage_timing_disable();
+            return fail(MOE_ERR_HIP, "hipEventCreate failed: %s", hipGetErrorString(e));
+        }
+    }
+    g_timer.n = 0;
+    g_timer.on = true;
+    return MOE_OK;
+}
+
+int moe_stage_timing_read(float* ms, int32_t capacity_calls, int32_t* n_calls) {
+    REQUIRE(n_calls, "n_calls");
+    *n_calls = g_timer.n;
+    if (ms == nullptr) return MOE_OK;
+    const int n = g_timer.n < capacity_calls ? g_timer.n : capacity_calls;
+    for (int c = 0; c < n; ++c) {
+        hipEvent_t* ev = g_timer.ev + kStageEvents * c;
+        MOE_HIP_CHECK(hipEventSynchronize(ev[kStageEvents - 1]));
+        for (int st = 0; st + 1 < kStageEvents; ++st)
+            MOE_HIP_CHECK(hipEventElapsedTime(&ms[c * (kStageEvents - 1) + st], ev[st], ev[st + 1]));
+    }
+    return MOE_OK;
+}
+
+int moe_stage_timing_disable(void) {
+    if (g_timer.ev != nullptr) {
+        for (int i = 0; i < g_timer.cap * kStageEvents; ++i)
+            if (g_timer.ev[i]) (void)hipEventDestroy(g_timer.ev[i]);
+        delete[] g_timer.ev;
+    }
+    g_timer = StageTimer();
+    return MOE_OK;
 }
 
 int moe_stream_ctx_create(const moe_cfg* cfg, const void* host_experts, size_t expert_bytes, void* dev_slots,

@@ -63,8 +63,10 @@ int launch_pack(const moe_cfg& c, const void* Win, const void* Wgate, const void
 // Runs the FFN of experts [e_first, e_first + e_count); W points at the packed block of e_first and
 // consecutive experts are expert_stride_bytes apart.  max_rows bounds the rows those experts can hold
 // (it sizes the grid; blocks past the real row count exit).
+// `between`, if not null, is recorded on `s` after the up kernel and before the down kernel.
 int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, int e_first, int e_count,
-                      const void* W, size_t expert_stride_bytes, long max_rows, void* H, void* Yp, hipStream_t s);
+                      const void* W, size_t expert_stride_bytes, long max_rows, void* H, void* Yp, hipStream_t s,
+                      hipEvent_t between = nullptr);
 int launch_combine(const moe_cfg& c, const void* Yp, const int32_t* inv, const float* w, void* y, hipStream_t s);
 
 }  // namespace moe

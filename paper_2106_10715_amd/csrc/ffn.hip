@@ -341,7 +341,8 @@ int launch_pack(const moe_cfg& c, const void* Win, const void* Wgate, const void
 }
 
 int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, int e_first, int e_count,
-                      const void* W, size_t expert_stride_bytes, long max_rows, void* H, void* Yp, hipStream_t s) {
+                      const void* W, size_t expert_stride_bytes, long max_rows, void* H, void* Yp, hipStream_t s,
+                      hipEvent_t between) {
     if (max_rows <= 0 || e_count <= 0) return MOE_OK;
     const size_t df = static_cast<size_t>(c.d) * c.f;
     if (c.dtype == MOE_BF16) {
@@ -354,6 +355,7 @@ int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, 
                            e_count, static_cast<const char*>(W), expert_stride_bytes, size_t(0),
                            static_cast<uint16_t*>(H), c.d, c.f, c.act);
         MOE_LAUNCH_CHECK("ffn_mfma_kernel<up>");
+        if (between != nullptr) MOE_HIP_CHECK(hipEventRecord(between, s));
         dim3 grid_dn((c.d / 64 + 3) / 4, static_cast<unsigned>(slots));
         hipLaunchKernelGGL(ffn_mfma_kernel<false>, grid_dn, block, 0, s, static_cast<const uint16_t*>(H), offsets, e_first,
                            e_count, static_cast<const char*>(W), expert_stride_bytes, down_off,
@@ -369,6 +371,7 @@ int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, 
                        static_cast<const float*>(Xp), offsets, e_first, e_count, Wf, stride, size_t(0), df,
                        static_cast<float*>(H), c.d, c.f, c.act);
     MOE_LAUNCH_CHECK("ffn_f32_kernel<up>");
+    if (between != nullptr) MOE_HIP_CHECK(hipEventRecord(between, s));
     hipLaunchKernelGGL(ffn_f32_kernel<false>, dim3(c.d / kF32Tile, static_cast<unsigned>(slots)), dim3(256), 0, s,
                        static_cast<const float*>(H), offsets, e_first, e_count, Wf, stride, 2 * df, 2 * df,
                        static_cast<float*>(Yp), c.f, c.d, c.act);
