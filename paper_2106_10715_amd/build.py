@@ -23,9 +23,14 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
+# ffn.hip spells out its software pipeline (loads first, LDS reads one k-step ahead of the MFMAs); the
+# machine scheduler would fold that back into load-use pairs to save registers, so it is switched off there.
+EXTRA = {"ffn.hip": ["-mllvm", "-enable-misched=false"]}
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(HERE, "_build", src.replace(".hip", ".o"))
-    cmd = [_hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [_hipcc(), *FLAGS, *EXTRA.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)

@@ -36,7 +36,7 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // Assignments handled by one block of the histogram / scatter kernels of the permutation.
 constexpr int kPermChunk = 1024;
 // Rows of one expert segment covered by one block of the FFN kernels.
-constexpr int kTileM = 128;
+constexpr int kTileM = 256;
 
 // Byte offsets of every region inside the caller's workspace.
 struct WsLayout {

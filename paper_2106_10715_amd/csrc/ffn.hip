@@ -5,11 +5,11 @@
 //     H  = act(Xp W_gate[e]) * (Xp W_in[e])        "up"   grouped GEMM, epilogue fused
 //     Yp = H W_out[e]                               "down" grouped GEMM
 //
-// bf16 path: 32x32x16 bf16 MFMA, fp32 accumulate.  One block = 128 rows of one expert x 4 waves;
-// every wave owns its own output columns for all 128 rows, so a weight fragment is needed by exactly
+// bf16 path: 32x32x16 bf16 MFMA, fp32 accumulate.  One block = up to 256 rows of one expert x 4 waves;
+// every wave owns its own output columns for all rows, so a weight fragment is needed by exactly
 // one wave: weights go HBM -> registers directly in pre-packed fragment order (no LDS, fully
-// coalesced 1 KiB reads), only the activation tile is shared through LDS (stored in fragment order,
-// conflict-free 16-byte reads).  With few rows per expert the layer is bound by streaming the
+// coalesced 1 KiB reads), only the activation tile is shared through LDS (padded rows,
+// conflict-free 16-byte reads and writes).  With few rows per expert the layer is bound by streaming the
 // weights once from HBM, which is what this layout is built for.
 // fp32 path: plain LDS-tiled FMA kernel (small-shape correctness vehicle).
 #include "common.h"
@@ -21,7 +21,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kKC = 64;                 // reduction elements staged per pipeline step (4 MFMA k-steps)
-constexpr int kMB = kTileM / 32;        // 32-row MFMA blocks per tile
 
 __device__ inline float act_fn(float z, int act) {
     if (act == 0) return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
@@ -29,10 +28,10 @@ __device__ inline float act_fn(float z, int act) {
     return 0.5f * z * (1.0f + tanhf(u));
 }
 
-// Which (expert, row tile) a block works on: tile slot blockIdx.y counted over the experts
+// Which (expert, row tile) a block works on: tile slot `slot` counted over the experts
 // [e_first, e_first + e_count) in order, tile_m rows per tile.  Returns false when the slot is past
 // the last tile (uniform for the block).  Must be called by all threads of the block.
-__device__ inline bool find_tile(const int32_t* __restrict__ offsets, int e_first, int e_count, int tile_m,
+__device__ inline bool find_tile(const int32_t* __restrict__ offsets, int e_first, int e_count, int tile_m, int slot,
                                  int& e_out, int& row_begin, int& rows) {
     __shared__ int sh_e, sh_mt;
     if (threadIdx.x < 64) {
@@ -51,7 +50,7 @@ __device__ inline bool find_tile(const int32_t* __restrict__ offsets, int e_firs
             const int v = __shfl_up(incl, off);
             if (lane >= off) incl += v;
         }
-        const int target = blockIdx.y;
+        const int target = slot;
         int run = incl - sum;
         if (target >= run && target < incl) {
 #pragma unroll
@@ -116,120 +115,194 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint16_t* __restri
 }
 
 // ------------------------------------------------------------------------------------------ bf16 MFMA
+//
+// Software pipeline of one block (4 waves, up to 256 rows of one expert, 64 reduction elements per
+// step).  In step c every thread
+//     issues its share of the activation tile of step c+1            (global -> registers)
+//     issues its wave's weight fragments of step c+2                 (global -> registers, ring of 3)
+//     runs the MFMAs of step c (weights from the ring, activations from LDS buffer c%2, the LDS
+//         reads of k-step s+1 overlapping the MFMAs of k-step s)
+//     waits for the activation registers, stores them to LDS buffer (c+1)%2, barrier.
+// The compiler would sink all those loads down to their first use and wait there, which serialises
+// the pipeline, and it removes prefetches whose result is never read, which changes how many loads
+// are in flight.  So every global load of the loop is issued from inline assembly (pinned in program
+// order, never removed) and the one wait per step is written by hand: vector memory loads return in
+// order, hence "at most 4*NF loads outstanding" at the end of step c means everything but the weight
+// fragments issued in this very step has arrived -- the activations of step c+1 and, being older, the
+// weights of step c+1.  The wait names those registers as read-write operands so that no use of them
+// can be moved above it.
 
-struct BFrags { uint4 v[kKC / 16][2]; };   // one pipeline step of one wave: 4 k-steps x 2 fragments
+constexpr int kKS = kKC / 16;           // MFMA k-steps per pipeline step
+constexpr int kRing = 3;                // weight-fragment register buffers
+constexpr int kLdsRow = 9;              // uint4 per activation row in LDS: 128 B of data + 16 B pad (conflict-free)
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int NF>
+struct BFrags { u32x4 v[kKS][NF]; };    // one pipeline step of one wave: 4 k-steps x NF fragments
+template <int MBS>
+struct ARegs { u32x4 v[MBS]; };         // this thread's share of one activation tile step
+
+__device__ inline bf16x8 as_bf16x8(const u32x4& u) { return __builtin_bit_cast(bf16x8, u); }
 __device__ inline bf16x8 as_bf16x8(const uint4& u) { return __builtin_bit_cast(bf16x8, u); }
 
-__device__ inline void load_b(BFrags& b, const uint4* __restrict__ wave_w, int chunk, int lane) {
-    // fragments of one (column unit, k-step) are adjacent: [k-step][2][64 lanes] x 16 bytes
-    const uint4* p = wave_w + static_cast<size_t>(chunk) * (kKC / 16) * 128 + lane;
-#pragma unroll
-    for (int ks = 0; ks < kKC / 16; ++ks) {
-        b.v[ks][0] = p[ks * 128];
-        b.v[ks][1] = p[ks * 128 + 64];
-    }
+// 16-byte load from (uniform base + per-lane byte offset + immediate), pinned in program order.
+template <int IMM>
+__device__ inline void ld_pinned(u32x4& dst, uint32_t voff, const void* sbase) {
+    asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3" : "=v"(dst) : "v"(voff), "s"(sbase), "n"(IMM) : "memory");
 }
 
-struct ARegs { uint4 v[kMB]; };             // this thread's share of one activation tile step
-
-__device__ inline void load_a(ARegs& a, const uint16_t* __restrict__ A, int K, int row_begin, int rows, int chunk,
-                              int wave, int lane) {
-    // thread (wave, lane) fetches, for each 32-row block mb, row mb*32 + lane%32, 8 elements at
-    // k = chunk*64 + wave*16 + 8*(lane/32): exactly LDS slot (mb, k-step = wave, lane) of the fragment order
-    const int kcol = chunk * kKC + wave * 16 + 8 * (lane >> 5);
-#pragma unroll
-    for (int mb = 0; mb < kMB; ++mb) {
-        const int r = mb * 32 + (lane & 31);
-        if (r < rows)
-            a.v[mb] = *reinterpret_cast<const uint4*>(A + static_cast<size_t>(row_begin + r) * K + kcol);
-        else
-            a.v[mb] = make_uint4(0, 0, 0, 0);
-    }
+// The two fragments of one (column unit, k-step) are adjacent in the packed block:
+// [k-step][2][64 lanes] x 16 bytes (2 KiB per k-step); a wave with NF = 1 reads one of the two.
+// voff = byte offset of this lane inside its wave's stream at the first k-step of the pipeline step.
+template <int NF>
+__device__ inline void load_b(BFrags<NF>& b, uint32_t voff, const void* wave_base) {
+    ld_pinned<0>(b.v[0][0], voff, wave_base);
+    if (NF == 2) ld_pinned<1024>(b.v[0][NF - 1], voff, wave_base);
+    ld_pinned<2048>(b.v[1][0], voff, wave_base);
+    if (NF == 2) ld_pinned<3072>(b.v[1][NF - 1], voff, wave_base);
+    const uint32_t voff2 = voff + 4096;
+    ld_pinned<0>(b.v[2][0], voff2, wave_base);
+    if (NF == 2) ld_pinned<1024>(b.v[2][NF - 1], voff2, wave_base);
+    ld_pinned<2048>(b.v[3][0], voff2, wave_base);
+    if (NF == 2) ld_pinned<3072>(b.v[3][NF - 1], voff2, wave_base);
 }
 
-__device__ inline void store_a(const ARegs& a, uint4* lds_buf, int wave, int lane) {
+// End-of-step wait: at most 4*NF loads (this step's weight prefetch) may still be outstanding.
+template <int NF, int MBS>
+__device__ inline void wait_step(ARegs<MBS>& a, BFrags<NF>& next) {
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(kKS * NF) : "memory");
 #pragma unroll
-    for (int mb = 0; mb < kMB; ++mb) lds_buf[(mb * (kKC / 16) + wave) * 64 + lane] = a.v[mb];
+    for (int mb = 0; mb < MBS; ++mb) asm volatile("" : "+v"(a.v[mb]));
+#pragma unroll
+    for (int ks = 0; ks < kKS; ++ks)
+#pragma unroll
+        for (int j = 0; j < NF; ++j) asm volatile("" : "+v"(next.v[ks][j]));
 }
 
-__device__ inline void mma_step(f32x16 (&acc)[kMB][2], const uint4* lds_buf, const BFrags& b, int lane) {
+// The activation tile lives in LDS row-major, one padded row of kLdsRow uint4 per tile row.
+// Staging: thread t moves, for i < MBS, the 16-byte piece (row i*32 + t/8, piece t%8): eight
+// neighbouring lanes fetch one whole 128-byte line of a row, and write 128 contiguous bytes of LDS.
+template <int MBS>
+__device__ inline void store_a(const ARegs<MBS>& a, uint4* lds_buf) {
+    u32x4* p = reinterpret_cast<u32x4*>(lds_buf) + (threadIdx.x >> 3) * kLdsRow + (threadIdx.x & 7);
 #pragma unroll
-    for (int ks = 0; ks < kKC / 16; ++ks) {
-        bf16x8 af[kMB];
+    for (int mb = 0; mb < MBS; ++mb) p[mb * 32 * kLdsRow] = a.v[mb];
+}
+
+// One pipeline step: 4 k-steps of MBS x NF MFMAs.  The A fragments of the next k-step are read from
+// LDS while the MFMAs of the current one run.  Fragment (mb, ks) of lane l = row mb*32 + l%32,
+// 8 elements at k = 16 ks + 8 (l / 32).
+template <int NF, int MBS>
+__device__ inline void mma_step(f32x16 (&acc)[MBS][NF], const uint4* lds_buf, const BFrags<NF>& b, int lane) {
+    const uint4* rp = lds_buf + (lane & 31) * kLdsRow + (lane >> 5);
+    uint4 af[2][MBS];
 #pragma unroll
-        for (int mb = 0; mb < kMB; ++mb) af[mb] = as_bf16x8(lds_buf[(mb * (kKC / 16) + ks) * 64 + lane]);
-        const bf16x8 b0 = as_bf16x8(b.v[ks][0]), b1 = as_bf16x8(b.v[ks][1]);
+    for (int mb = 0; mb < MBS; ++mb) af[0][mb] = rp[mb * 32 * kLdsRow];
 #pragma unroll
-        for (int mb = 0; mb < kMB; ++mb) {
-            acc[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mb], b0, acc[mb][0], 0, 0, 0);
-            acc[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mb], b1, acc[mb][1], 0, 0, 0);
+    for (int ks = 0; ks < kKS; ++ks) {
+        if (ks + 1 < kKS) {
+#pragma unroll
+            for (int mb = 0; mb < MBS; ++mb) af[(ks + 1) & 1][mb] = rp[mb * 32 * kLdsRow + 2 * (ks + 1)];
+        }
+#pragma unroll
+        for (int mb = 0; mb < MBS; ++mb) {
+#pragma unroll
+            for (int j = 0; j < NF; ++j)
+                acc[mb][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af[ks & 1][mb]), as_bf16x8(b.v[ks][j]),
+                                                                     acc[mb][j], 0, 0, 0);
         }
     }
 }
 
-// C[rows of one expert tile, N] = A[rows, K] * B_e, B_e in packed fragment order.
-// GATED: every wave unit is 32 output columns whose two fragments per k-step are (W_gate, W_in);
-//        the epilogue writes act(gate) * in.   Otherwise a unit is 64 output columns.
-template <bool GATED>
-__global__ __launch_bounds__(256) void ffn_mfma_kernel(const uint16_t* __restrict__ A, const int32_t* __restrict__ offsets,
-                                                       int e_first, int e_count, const char* __restrict__ W,
-                                                       size_t expert_stride_bytes, size_t block_offset_bytes,
-                                                       uint16_t* __restrict__ C, int K, int N, int act) {
-    __shared__ uint4 lds[2][kMB * (kKC / 16) * 64];   // 2 x 16 KiB activation tiles in fragment order
-    int e, row_begin, rows;
-    if (!find_tile(offsets, e_first, e_count, kTileM, e, row_begin, rows)) return;
+// One tile of MBS 32-row blocks: the whole reduction loop and the epilogue.
+// Loads past the end are clamped to valid addresses (rows to the last row of the tile, pipeline steps
+// to the last step) instead of being skipped, so every step issues the same loads.  Rows that are
+// clamped duplicates only produce output rows that are never stored (an output row depends on its own
+// input row only).
+template <bool GATED, int NF, int MBS>
+__device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_t* __restrict__ A, int row_begin, int rows,
+                                const void* wave_base, uint16_t* __restrict__ C, int K, int N, int unit,
+                                bool active, int act, unsigned phase_key) {
+    const int lane = threadIdx.x & 63;
+    const int chunks = K / kKC, last = chunks - 1;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int unit_cols = GATED ? 32 : 64;
-    const int units = N / unit_cols;
-    const int unit = blockIdx.x * 4 + wave;
-    const bool active = unit < units;              // idle waves still help staging the activation tile
-    const int steps16 = K / 16;
-    const uint4* wave_w = reinterpret_cast<const uint4*>(W + static_cast<size_t>(e - e_first) * expert_stride_bytes +
-                                                         block_offset_bytes) +
-                          static_cast<size_t>(active ? unit : 0) * steps16 * 128;
-    const int chunks = K / kKC;
+    // this thread's activation sources (byte offsets from A): row mb*32 + t/8 of every block, piece t%8;
+    // rows past the tile end re-read the last row
+    const int r0 = threadIdx.x >> 3;
+    uint32_t a_off[MBS];
+#pragma unroll
+    for (int mb = 0; mb < MBS; ++mb)
+        a_off[mb] = (static_cast<uint32_t>(row_begin + min(mb * 32 + r0, rows - 1)) * K + 8 * (threadIdx.x & 7)) * 2u;
 
-    f32x16 acc[kMB][2];
+    f32x16 acc[MBS][NF];
 #pragma unroll
-    for (int mb = 0; mb < kMB; ++mb)
+    for (int mb = 0; mb < MBS; ++mb)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NF; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mb][j][v] = 0.f;
 
-    ARegs areg;
-    BFrags b0, b1;
-    load_a(areg, A, K, row_begin, rows, 0, wave, lane);
-    if (active) load_b(b0, wave_w, 0, lane);
-    store_a(areg, lds[0], wave, lane);
+    ARegs<MBS> areg;
+    BFrags<NF> ring[kRing];
+    auto fetch_a = [&](int chunk) {
+        const uint32_t step_off = static_cast<uint32_t>(chunk) * (kKC * 2);
+#pragma unroll
+        for (int mb = 0; mb < MBS; ++mb) ld_pinned<0>(areg.v[mb], a_off[mb] + step_off, A);
+    };
+    auto fetch_b = [&](BFrags<NF>& dst, int chunk) {
+        load_b(dst, static_cast<uint32_t>(chunk) * (kKS * 2048) + lane * 16, wave_base);
+    };
+    // Blocks that run at the same time start their sweep over the reduction dimension at different
+    // steps (and wrap around), so that concurrent waves do not walk their weight streams, which lie a
+    // power of two apart, in lockstep.  The phase depends only on (expert, row tile, column group),
+    // never on the launch shape, so a launch over all experts and a launch over one expert sum in the
+    // same order (bitwise equal results).
+    const int phase = static_cast<int>(phase_key % static_cast<unsigned>(chunks));
+    auto at = [&](int i) { const int c = phase + i; return c >= chunks ? c - chunks : c; };   // i < chunks
+    fetch_a(at(0));
+    fetch_b(ring[0], at(0));
+    fetch_b(ring[1], at(min(1, last)));
+    wait_step(areg, ring[0]);                  // everything but the newest weight step has landed
+    store_a(areg, lds[0]);
     __syncthreads();
 
-    // two pipeline steps per iteration so the fragment registers ping-pong without copies
-    int c = 0;
-    for (; c + 1 < chunks; c += 2) {
-        load_a(areg, A, K, row_begin, rows, c + 1, wave, lane);
-        if (active) load_b(b1, wave_w, c + 1, lane);
-        if (active) mma_step(acc, lds[0], b0, lane);
-        store_a(areg, lds[1], wave, lane);
-        __syncthreads();
-        const bool more = c + 2 < chunks;
-        if (more) {
-            load_a(areg, A, K, row_begin, rows, c + 2, wave, lane);
-            if (active) load_b(b0, wave_w, c + 2, lane);
-        }
-        if (active) mma_step(acc, lds[1], b1, lane);
-        if (more) store_a(areg, lds[0], wave, lane);
-        __syncthreads();
+#define FFN_STEP(I)                                                                   \
+    {                                                                                 \
+        const int ci = c + (I);                                                       \
+        fetch_a(at(min(ci + 1, last)));                                               \
+        fetch_b(ring[((I) + 2) % kRing], at(min(ci + 2, last)));                      \
+        mma_step(acc, lds[(ci) & 1], ring[(I)], lane);                                \
+        wait_step(areg, ring[((I) + 1) % kRing]);                                     \
+        store_a(areg, lds[(ci + 1) & 1]);                                             \
+        __syncthreads();                                                              \
     }
-    if (c < chunks && active) mma_step(acc, lds[0], b0, lane);   // odd number of steps: last one is staged in lds[0]
+    int c = 0;
+    for (; c + kRing <= chunks; c += kRing) {
+        FFN_STEP(0) FFN_STEP(1) FFN_STEP(2)
+    }
+    const int left = chunks - c;               // 0..2 steps that do not fill a group
+    if (left > 0) FFN_STEP(0)
+    if (left > 1) FFN_STEP(1)
+#undef FFN_STEP
+    // Drain the prefetches nobody consumes, and only then let go of their destination registers: a
+    // destination the compiler considers dead would be handed to something else (an LDS read, say)
+    // while the load into it is still in flight.
+    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
+#pragma unroll
+    for (int r = 0; r < kRing; ++r)
+#pragma unroll
+        for (int ks = 0; ks < kKS; ++ks)
+#pragma unroll
+            for (int j = 0; j < NF; ++j) asm volatile("" : : "v"(ring[r].v[ks][j]));
+#pragma unroll
+    for (int mb = 0; mb < MBS; ++mb) asm volatile("" : : "v"(areg.v[mb]));
     if (!active) return;
 
     // accumulator layout of the 32x32 MFMA: lane holds column lane%32, rows 8*(v/4) + 4*(lane/32) + v%4
     const int col_in = lane & 31, row_in = 4 * (lane >> 5);
 #pragma unroll
-    for (int mb = 0; mb < kMB; ++mb) {
+    for (int mb = 0; mb < MBS; ++mb) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int r = mb * 32 + 8 * (v >> 2) + row_in + (v & 3);
@@ -239,11 +312,61 @@ __global__ __launch_bounds__(256) void ffn_mfma_kernel(const uint16_t* __restric
                     const float h = act_fn(acc[mb][0][v], act) * acc[mb][1][v];
                     crow[unit * 32 + col_in] = __builtin_bit_cast(uint16_t, static_cast<__bf16>(h));
                 } else {
-                    crow[unit * 64 + col_in] = __builtin_bit_cast(uint16_t, static_cast<__bf16>(acc[mb][0][v]));
-                    crow[unit * 64 + 32 + col_in] = __builtin_bit_cast(uint16_t, static_cast<__bf16>(acc[mb][1][v]));
+#pragma unroll
+                    for (int j = 0; j < NF; ++j)
+                        crow[unit * 32 * NF + 32 * j + col_in] =
+                            __builtin_bit_cast(uint16_t, static_cast<__bf16>(acc[mb][j][v]));
                 }
             }
         }
+    }
+}
+
+// C[rows of one expert tile, N] = A[rows, K] * B_e, B_e in packed fragment order.
+// A block is up to 256 rows of one expert (only the 32-row blocks that hold rows are computed) by
+// 4 waves; wave w owns column unit blockIdx.y*4 + w for all rows.
+// GATED (NF = 2): a unit is 32 output columns whose two fragments per k-step are (W_gate, W_in); the
+//   epilogue writes act(gate) * in.
+// otherwise a unit is 32 * NF output columns of W_out.
+// Weight fragments stream HBM -> registers through a ring of kRing buffers so that several KiB per
+// wave are always in flight; the activation tile goes through LDS, double buffered.
+template <bool GATED, int NF>
+__global__ __launch_bounds__(256) void ffn_mfma_kernel(const uint16_t* __restrict__ A, const int32_t* __restrict__ offsets,
+                                                       int e_first, int e_count, const char* __restrict__ W,
+                                                       size_t expert_stride_bytes, size_t block_offset_bytes,
+                                                       uint16_t* __restrict__ C, int K, int N, int act) {
+    __shared__ uint4 lds[2][kTileM * kLdsRow];     // 2 x 36 KiB activation tiles, padded rows
+    int e, row_begin, rows;
+    if (!find_tile(offsets, e_first, e_count, kTileM, blockIdx.x, e, row_begin, rows)) return;
+
+    const int wave = threadIdx.x >> 6;
+    const int units = N / (32 * (GATED ? 1 : NF));
+    const int unit = blockIdx.y * 4 + wave;
+    const bool active = unit < units;              // a wave past the last unit recomputes the last one, stores nothing
+    const int u = active ? unit : units - 1;
+    const int steps16 = K / 16;
+    // fragment pair index and which half of the pair this wave reads
+    const int pair = (GATED || NF == 2) ? u : (u >> 1);
+    const int half = (GATED || NF == 2) ? 0 : (u & 1);
+    // start of this wave's fragment stream; the same for all lanes, so it is handed over in scalar registers
+    const char* wb = W + static_cast<size_t>(e - e_first) * expert_stride_bytes + block_offset_bytes +
+                     (static_cast<size_t>(pair) * steps16 * 128 + half * 64) * 16;
+    const uintptr_t wbi = reinterpret_cast<uintptr_t>(wb);
+    const uint32_t wb_lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(wbi))));
+    const uint32_t wb_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(wbi >> 32))));
+    const void* wave_w = reinterpret_cast<const void*>((static_cast<uintptr_t>(wb_hi) << 32) | static_cast<uintptr_t>(wb_lo));
+    const unsigned col_group = (GATED || NF == 2) ? blockIdx.y : (blockIdx.y >> 1);   // same for both unit widths
+    const unsigned key = static_cast<unsigned>(e) * 37u + static_cast<unsigned>(row_begin - offsets[e]) / kTileM * 11u +
+                         col_group * 17u;
+    switch ((rows + 31) >> 5) {
+        case 1: ffn_tile<GATED, NF, 1>(lds, A, row_begin, rows, wave_w, C, K, N, unit, active, act, key); break;
+        case 2: ffn_tile<GATED, NF, 2>(lds, A, row_begin, rows, wave_w, C, K, N, unit, active, act, key); break;
+        case 3: ffn_tile<GATED, NF, 3>(lds, A, row_begin, rows, wave_w, C, K, N, unit, active, act, key); break;
+        case 4: ffn_tile<GATED, NF, 4>(lds, A, row_begin, rows, wave_w, C, K, N, unit, active, act, key); break;
+        case 5: ffn_tile<GATED, NF, 5>(lds, A, row_begin, rows, wave_w, C, K, N, unit, active, act, key); break;
+        case 6: ffn_tile<GATED, NF, 6>(lds, A, row_begin, rows, wave_w, C, K, N, unit, active, act, key); break;
+        case 7: ffn_tile<GATED, NF, 7>(lds, A, row_begin, rows, wave_w, C, K, N, unit, active, act, key); break;
+        default: ffn_tile<GATED, NF, 8>(lds, A, row_begin, rows, wave_w, C, K, N, unit, active, act, key); break;
     }
 }
 
@@ -260,7 +383,7 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ 
     __shared__ float B0s[16][kF32Tile + 4];
     __shared__ float B1s[GATED ? 16 : 1][kF32Tile + 4];
     int e, row_begin, rows;
-    if (!find_tile(offsets, e_first, e_count, kF32Tile, e, row_begin, rows)) return;
+    if (!find_tile(offsets, e_first, e_count, kF32Tile, blockIdx.y, e, row_begin, rows)) return;
     const float* B0 = W + static_cast<size_t>(e - e_first) * expert_stride_elems + off_b0;
     const float* B1 = W + static_cast<size_t>(e - e_first) * expert_stride_elems + off_b1;
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
@@ -346,20 +469,33 @@ int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, 
     if (max_rows <= 0 || e_count <= 0) return MOE_OK;
     const size_t df = static_cast<size_t>(c.d) * c.f;
     if (c.dtype == MOE_BF16) {
-        const long slots = max_rows / kTileM + e_count;
-        if (slots > 65535) return fail(MOE_ERR_UNSUPPORTED, "too many row tiles for one launch (%ld)", slots);
+        // grid.x = row-tile slots (fastest varying, padded to the 8 XCDs so that the blocks sharing one
+        // activation tile land on one XCD and its L2), grid.y = groups of 4 column units
+        long slots = max_rows / kTileM + e_count;
+        slots = (slots + 7) / 8 * 8;
+        if (slots > 0x7fffffffL) return fail(MOE_ERR_UNSUPPORTED, "too many row tiles for one launch (%ld)", slots);
         const size_t down_off = 2 * df * 2;
         dim3 block(256);
-        dim3 grid_up((c.f / 32 + 3) / 4, static_cast<unsigned>(slots));
-        hipLaunchKernelGGL(ffn_mfma_kernel<true>, grid_up, block, 0, s, static_cast<const uint16_t*>(Xp), offsets, e_first,
-                           e_count, static_cast<const char*>(W), expert_stride_bytes, size_t(0),
+        dim3 grid_up(static_cast<unsigned>(slots), (c.f / 32 + 3) / 4);
+        hipLaunchKernelGGL((ffn_mfma_kernel<true, 2>), grid_up, block, 0, s, static_cast<const uint16_t*>(Xp), offsets,
+                           e_first, e_count, static_cast<const char*>(W), expert_stride_bytes, size_t(0),
                            static_cast<uint16_t*>(H), c.d, c.f, c.act);
         MOE_LAUNCH_CHECK("ffn_mfma_kernel<up>");
         if (between != nullptr) MOE_HIP_CHECK(hipEventRecord(between, s));
-        dim3 grid_dn((c.d / 64 + 3) / 4, static_cast<unsigned>(slots));
-        hipLaunchKernelGGL(ffn_mfma_kernel<false>, grid_dn, block, 0, s, static_cast<const uint16_t*>(H), offsets, e_first,
-                           e_count, static_cast<const char*>(W), expert_stride_bytes, down_off,
-                           static_cast<uint16_t*>(Yp), c.f, c.d, c.act);
+        // down-projection: narrow (32-column) units when wide ones would leave compute units idle
+        const long tiles_hint = (max_rows + kTileM - 1) / kTileM > e_count ? (max_rows + kTileM - 1) / kTileM : e_count;
+        const bool narrow = tiles_hint * ((c.d / 64 + 3) / 4) < 2 * 256;
+        if (narrow) {
+            dim3 grid_dn(static_cast<unsigned>(slots), (c.d / 32 + 3) / 4);
+            hipLaunchKernelGGL((ffn_mfma_kernel<false, 1>), grid_dn, block, 0, s, static_cast<const uint16_t*>(H), offsets,
+                               e_first, e_count, static_cast<const char*>(W), expert_stride_bytes, down_off,
+                               static_cast<uint16_t*>(Yp), c.f, c.d, c.act);
+        } else {
+            dim3 grid_dn(static_cast<unsigned>(slots), (c.d / 64 + 3) / 4);
+            hipLaunchKernelGGL((ffn_mfma_kernel<false, 2>), grid_dn, block, 0, s, static_cast<const uint16_t*>(H), offsets,
+                               e_first, e_count, static_cast<const char*>(W), expert_stride_bytes, down_off,
+                               static_cast<uint16_t*>(Yp), c.f, c.d, c.act);
+        }
         MOE_LAUNCH_CHECK("ffn_mfma_kernel<down>");
         return MOE_OK;
     }
