@@ -55,6 +55,7 @@ WsLayout ws_layout(const moe_cfg& c) {
     L.perm = take(A * 4);
     L.inv = take(A * 4);
     L.chunk_hist = take((chunks > 0 ? chunks : 1) * c.E * 4);
+    L.route = take(route_scratch_bytes(c));
     L.total = at > 0 ? at : 256;
     return L;
 }
@@ -124,11 +125,13 @@ int moe_pack_weights(const moe_cfg* cfg, const void* W_in_e, const void* W_gate_
 
 int moe_route(const moe_cfg* cfg, const void* x, const void* W_g, const float* gate_bias, int32_t* idx, float* w,
               void* ws, void* stream) {
-    (void)ws;
     if (int rc = check_cfg(cfg)) return rc;
     REQUIRE(W_g, "W_g");
-    if (cfg->T > 0) { REQUIRE(x, "x"); REQUIRE(idx, "idx"); REQUIRE(w, "w"); }
-    return launch_route(*cfg, x, W_g, gate_bias, idx, w, static_cast<hipStream_t>(stream));
+    if (cfg->T == 0) return MOE_OK;
+    REQUIRE(x, "x"); REQUIRE(idx, "idx"); REQUIRE(w, "w"); REQUIRE(ws, "ws");
+    REQUIRE_ALIGNED(x, "x"); REQUIRE_ALIGNED(ws, "ws");
+    return launch_route(*cfg, x, W_g, gate_bias, idx, w, static_cast<char*>(ws) + ws_layout(*cfg).route,
+                        static_cast<hipStream_t>(stream));
 }
 
 int moe_permute(const moe_cfg* cfg, const void* x, const int32_t* idx, int32_t* counts, int32_t* offsets,
@@ -197,7 +200,7 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
     hipEvent_t* tev = nullptr;     // this call's stage events, if stage timing is on and has room
     if (sctx == nullptr && g_timer.on && g_timer.n < g_timer.cap) tev = g_timer.ev + kStageEvents * g_timer.n++;
     if (tev) MOE_HIP_CHECK(hipEventRecord(tev[0], s));
-    if (int rc = launch_route(c, x, W_g, gate_bias, idx, w, s)) return rc;
+    if (int rc = launch_route(c, x, W_g, gate_bias, idx, w, base + L.route, s)) return rc;
     if (tev) MOE_HIP_CHECK(hipEventRecord(tev[1], s));
     if (int rc = launch_permute(c, x, idx, counts, offsets, perm, inv, base + L.Xp,
                                 reinterpret_cast<int32_t*>(base + L.chunk_hist), s))

@@ -50,13 +50,16 @@ struct WsLayout {
     size_t perm;       // [A] int32
     size_t inv;        // [A] int32
     size_t chunk_hist; // [chunks, E] int32: per-chunk expert histograms, then per-chunk bases
+    size_t route;      // gate projection in MFMA fragment order + per-group column sums of squares
     size_t total;
 };
 WsLayout ws_layout(const moe_cfg& c);
 
 // ---- launchers (each enqueues on `s` and returns MOE_OK or an error already recorded) ----
+// `scratch`: route_scratch_bytes(c) bytes of workspace (the gate re-packed for the matrix cores).
+size_t route_scratch_bytes(const moe_cfg& c);
 int launch_route(const moe_cfg& c, const void* x, const void* Wg, const float* bias, int32_t* idx, float* w,
-                 hipStream_t s);
+                 void* scratch, hipStream_t s);
 int launch_permute(const moe_cfg& c, const void* x, const int32_t* idx, int32_t* counts, int32_t* offsets,
                    int32_t* perm, int32_t* inv, void* Xp, int32_t* chunk_hist, hipStream_t s);
 int launch_pack(const moe_cfg& c, const void* Win, const void* Wgate, const void* Wout, void* packed, hipStream_t s);

@@ -51,6 +51,49 @@ __device__ inline void wave_topk(const double (&lv)[kNE], int eg, bool owner, in
     }
 }
 
+// Combine weights of one token from its ranked logits, written by lane 0.  lv: this lane's logits of
+// the experts it owns (only read for the full-softmax denominator).
+__device__ inline void emit_token(const double (&lv)[kNE], const double (&sv)[kSel], const int (&se)[kSel], int eg, bool owner,
+                                  int E, int k, int renorm, int lane, int32_t* __restrict__ idx_row, float* __restrict__ w_row) {
+    float wj[kSel];
+    float denom = 0.f;
+#pragma unroll
+    for (int r = 0; r < kSel; ++r)
+        if (r < k) wj[r] = expf(static_cast<float>(sv[r] - sv[0]));
+    if (renorm) {
+#pragma unroll
+        for (int r = 0; r < kSel; ++r)
+            if (r < k) denom += wj[r];
+    } else {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < kNE; ++i)
+            if (owner && eg + 64 * i < E) s += expf(static_cast<float>(lv[i] - sv[0]));
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+        denom = s;
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int r = 0; r < kSel; ++r)
+            if (r < k) {
+                idx_row[r] = se[r];
+                w_row[r] = wj[r] / denom;
+            }
+    }
+}
+
+// Smallest gap between consecutive ranks 0..kk-1 and the largest magnitude among them.
+__device__ inline void rank_gaps(const double (&sv)[kSel], int kk, double& gap, double& vmax) {
+    gap = INFINITY;
+    vmax = 0.0;
+#pragma unroll
+    for (int r = 0; r < kSel; ++r) {
+        if (r < kk) vmax = fmax(vmax, fabs(sv[r]));
+        if (r + 1 < kk) gap = fmin(gap, sv[r] - sv[r + 1]);
+    }
+}
+
 template <typename XT>
 __global__ __launch_bounds__(kWaves * 64) void route_kernel(const XT* __restrict__ x, const XT* __restrict__ Wg,
                                                             const float* __restrict__ bias,
@@ -158,12 +201,8 @@ __global__ __launch_bounds__(kWaves * 64) void route_kernel(const XT* __restrict
 
         // |computed - exact| <= n_round u |x_t| |W_g col| + u |logit| for every logit that matters
         // (Cauchy-Schwarz bounds the sum of |products|); 1/16 of slack covers the fp32 norms themselves.
-        double vmax = 0.0, gap = INFINITY;
-#pragma unroll
-        for (int r = 0; r < kSel; ++r) {
-            if (r < kk_sel) vmax = fmax(vmax, fabs(sv[r]));
-            if (r + 1 < kk_sel) gap = fmin(gap, sv[r] - sv[r + 1]);
-        }
+        double vmax, gap;
+        rank_gaps(sv, kk_sel, gap, vmax);
         const double delta = 1.0625 * 5.9604644775390625e-8 *
                              (static_cast<double>(n_round) * sqrt(static_cast<double>(xsq[tt]) * static_cast<double>(wn2)) + vmax);
         if (gap <= 2.0 * delta) {
@@ -187,49 +226,260 @@ __global__ __launch_bounds__(kWaves * 64) void route_kernel(const XT* __restrict
             wave_topk(lv, eg, owner, E, kk_sel, sv, se);
         }
 
-        // combine weights, fp32
-        float wj[kSel];
-        float denom = 0.f;
+        emit_token(lv, sv, se, eg, owner, E, k, renorm, lane, idx + static_cast<size_t>(t) * k,
+                   w + static_cast<size_t>(t) * k);
+    }
+}
+
+// ------------------------------------------------------------------------------------------ bf16: MFMA gate
+//
+// logits tile = 32 tokens x E on 32x32x16 bf16 MFMAs.  The four waves of a block split the reduction
+// dimension (wave w takes the 64-element groups S = w, w+4, ...), the partial tiles are added in wave
+// order through LDS.  W_g is first rewritten (gate_prep_kernel) into MFMA fragment order so that its
+// fragments are plain 1 KiB coalesced reads, and so that a lane's four fragments of a group use 64
+// contiguous bytes of its token row: fragment (nb, S, q), lane l, element j holds
+//     W_g[64 S + 32 (l / 32) + 8 q + j, 32 nb + l % 32]            (0 beyond E).
+//
+// Error bound of an MFMA logit (measured behaviour of the instruction: the addends of one
+// instruction -- accumulator and products -- are aligned to the largest of them and cut to fp32
+// precision, so one instruction loses at most 17 units in the last place of its largest addend, which
+// is at most the sum of |products|): |error| <= (17 n + 8) 2^-24 |x_t| |W_g column| with n the MFMAs a
+// wave chains per logit.  Tokens whose k+1 best logits are not separated by twice that are
+// re-evaluated in fp64 by the whole block.
+
+constexpr int kGateTokens = 32;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// Block b packs the 64-row group S = b of W_g for every 32-expert block and writes the sums of squares
+// of those 64 rows per expert column: part[b][E_pad].
+__global__ __launch_bounds__(256) void gate_prep_kernel(const uint16_t* __restrict__ Wg, int d, int E, int NB,
+                                                        uint4* __restrict__ pack, float* __restrict__ part) {
+    __shared__ float sq[4][32];
+    const int S = blockIdx.x, nS = d / 64;
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;      // wave q packs fragment q of the group
+    const int col_in = lane & 31, row0 = 64 * S + 32 * (lane >> 5) + 8 * q;
+    for (int nb = 0; nb < NB; ++nb) {
+        const int col = 32 * nb + col_in;
+        uint16_t v[8];
+        float ss = 0.f;
 #pragma unroll
-        for (int r = 0; r < kSel; ++r)
-            if (r < k) wj[r] = expf(static_cast<float>(sv[r] - sv[0]));
-        if (renorm) {
-#pragma unroll
-            for (int r = 0; r < kSel; ++r)
-                if (r < k) denom += wj[r];
-        } else {
-            float s = 0.f;
-#pragma unroll
-            for (int i = 0; i < kNE; ++i)
-                if (owner && eg + 64 * i < E) s += expf(static_cast<float>(lv[i] - sv[0]));
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
-            denom = s;
+        for (int j = 0; j < 8; ++j) {
+            v[j] = col < E ? Wg[static_cast<size_t>(row0 + j) * E + col] : uint16_t(0);
+            const float f = __uint_as_float(static_cast<uint32_t>(v[j]) << 16);
+            ss = fmaf(f, f, ss);
         }
-        if (lane == 0) {
+        uint4 o;
+        o.x = v[0] | (static_cast<uint32_t>(v[1]) << 16);
+        o.y = v[2] | (static_cast<uint32_t>(v[3]) << 16);
+        o.z = v[4] | (static_cast<uint32_t>(v[5]) << 16);
+        o.w = v[6] | (static_cast<uint32_t>(v[7]) << 16);
+        pack[((static_cast<size_t>(nb) * nS + S) * 4 + q) * 64 + lane] = o;
+        ss += __shfl_xor(ss, 32);
+        if (lane < 32) sq[q][lane] = ss;
+        __syncthreads();
+        if (threadIdx.x < 32)
+            part[static_cast<size_t>(S) * NB * 32 + col] = ((sq[0][col_in] + sq[1][col_in]) + sq[2][col_in]) + sq[3][col_in];
+        __syncthreads();
+    }
+}
+
+template <int NB>
+__global__ __launch_bounds__(256) void route_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wg,
+                                                         const uint4* __restrict__ pack, const float* __restrict__ part,
+                                                         const float* __restrict__ bias, int32_t* __restrict__ idx,
+                                                         float* __restrict__ w, int T, int d, int E, int k, int renorm) {
+    constexpr int EP = NB * 32;
+    __shared__ float logit[kGateTokens][EP + 1];
+    __shared__ float xsq_w[4][kGateTokens];
+    __shared__ float wn2_sh;
+    __shared__ int flagged[kGateTokens];
+    __shared__ double resc[4][EP];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t0 = blockIdx.x * kGateTokens;
+    const int nS = d / 64;
+
+    // ---- largest column norm of W_g: fixed-order sum of the per-group parts, then the block maximum
+    {
+        float best = 0.f;
+        for (int c = threadIdx.x; c < EP; c += 256) {
+            float ssum = 0.f;
+            for (int S = 0; S < nS; ++S) ssum += part[static_cast<size_t>(S) * EP + c];
+            best = fmaxf(best, ssum);
+        }
 #pragma unroll
-            for (int r = 0; r < kSel; ++r)
-                if (r < k) {
-                    idx[static_cast<size_t>(t) * k + r] = se[r];
-                    w[static_cast<size_t>(t) * k + r] = wj[r] / denom;
+        for (int off = 32; off >= 1; off >>= 1) best = fmaxf(best, __shfl_xor(best, off));
+        if (lane == 0) xsq_w[wave][0] = best;
+        __syncthreads();
+        if (threadIdx.x == 0) wn2_sh = fmaxf(fmaxf(xsq_w[0][0], xsq_w[1][0]), fmaxf(xsq_w[2][0], xsq_w[3][0]));
+        __syncthreads();
+    }
+
+    // ---- MFMA partial tiles
+    f32x16 acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[nb][v] = 0.f;
+    const int row = min(t0 + (lane & 31), T - 1);
+    const uint4* xrow = reinterpret_cast<const uint4*>(x + static_cast<size_t>(row) * d + 32 * (lane >> 5));
+    float xs = 0.f;
+    for (int S = wave; S < nS; S += 4) {
+        uint4 xa[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) xa[q] = xrow[S * 8 + q];          // 64 contiguous bytes of the token row
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t u[4] = {xa[q].x, xa[q].y, xa[q].z, xa[q].w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float lo = __uint_as_float(u[i] << 16), hi = __uint_as_float(u[i] & 0xffff0000u);
+                xs = fmaf(lo, lo, xs);
+                xs = fmaf(hi, hi, xs);
+            }
+        }
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const uint4* bp = pack + ((static_cast<size_t>(nb) * nS + S) * 4) * 64 + lane;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[q]),
+                                                                   __builtin_bit_cast(bf16x8, bp[q * 64]), acc[nb], 0, 0, 0);
+        }
+    }
+    xs += __shfl_xor(xs, 32);
+    if (lane < 32) xsq_w[wave][lane] = xs;
+    // partial tiles are added in wave order: ((w0 + w1) + w2) + w3
+    for (int turn = 0; turn < 4; ++turn) {
+        if (wave == turn) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int tok = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), e = 32 * nb + (lane & 31);
+                    logit[tok][e] = turn == 0 ? acc[nb][v] : logit[tok][e] + acc[nb][v];
                 }
         }
+        __syncthreads();
+    }
+
+    // ---- selection: wave w ranks tokens w, w+4, ...
+    const int n_chain = ((nS + 3) / 4) * 4;                               // MFMAs a wave chains per logit
+    const double gamma = 1.0625 * 5.9604644775390625e-8 * static_cast<double>(17 * n_chain + 8);
+    const int eg = lane;
+    const int kk_sel = min(k + 1, E);
+    float bl[kNE];
+#pragma unroll
+    for (int i = 0; i < kNE; ++i) bl[i] = (bias != nullptr && eg + 64 * i < E) ? bias[eg + 64 * i] : 0.f;
+    const double wn2 = static_cast<double>(wn2_sh);
+    for (int tt = wave; tt < kGateTokens; tt += 4) {
+        const int t = t0 + tt;
+        if (t >= T) { if (lane == 0) flagged[tt] = 0; continue; }
+        double lv[kNE];
+#pragma unroll
+        for (int i = 0; i < kNE; ++i) lv[i] = eg + 64 * i < E ? static_cast<double>(logit[tt][eg + 64 * i] + bl[i]) : 0.0;
+        double sv[kSel];
+        int se[kSel];
+        wave_topk(lv, eg, true, E, kk_sel, sv, se);
+        double gap, vmax;
+        rank_gaps(sv, kk_sel, gap, vmax);
+        const double xn2 = static_cast<double>(((xsq_w[0][tt] + xsq_w[1][tt]) + xsq_w[2][tt]) + xsq_w[3][tt]);
+        const double delta = gamma * sqrt(xn2 * wn2) + 1.0625 * 5.9604644775390625e-8 * vmax;
+        const bool close = gap <= 2.0 * delta;
+        if (lane == 0) flagged[tt] = close ? 1 : 0;
+        if (!close)
+            emit_token(lv, sv, se, eg, true, E, k, renorm, lane, idx + static_cast<size_t>(t) * k, w + static_cast<size_t>(t) * k);
+    }
+    __syncthreads();
+
+    // ---- fp64 re-evaluation of the tokens that were too close to call, by the whole block:
+    // wave w sums rows [w d/4, (w+1) d/4), the four partial sums are added in wave order.
+    int EPl = 1;
+    while (EPl < E && EPl < 64) EPl <<= 1;
+    const int KS = 64 / EPl, eg2 = lane & (EPl - 1), ks = lane / EPl;
+    for (int tt = 0; tt < kGateTokens; ++tt) {
+        if (!flagged[tt]) continue;                                      // uniform for the block
+        const int t = t0 + tt;
+        const uint16_t* xr = x + static_cast<size_t>(t) * d;
+        double a64[kNE];
+#pragma unroll
+        for (int i = 0; i < kNE; ++i) a64[i] = 0.0;
+        const int kend = (wave + 1) * (d / 4);
+        for (int kk = wave * (d / 4) + ks; kk < kend; kk += KS) {
+            const double xv = static_cast<double>(__uint_as_float(static_cast<uint32_t>(xr[kk]) << 16));
+#pragma unroll
+            for (int i = 0; i < kNE; ++i) {
+                const int ei = eg2 + 64 * i;
+                if (ei < E)
+                    a64[i] = fma(xv, static_cast<double>(__uint_as_float(static_cast<uint32_t>(Wg[static_cast<size_t>(kk) * E + ei]) << 16)),
+                                 a64[i]);
+            }
+        }
+        for (int off = EPl; off < 64; off <<= 1)
+#pragma unroll
+            for (int i = 0; i < kNE; ++i) a64[i] += __shfl_xor(a64[i], off);
+        if (ks == 0) {
+#pragma unroll
+            for (int i = 0; i < kNE; ++i)
+                if (eg2 + 64 * i < E) resc[wave][eg2 + 64 * i] = a64[i];
+        }
+        __syncthreads();
+        if (wave == 0) {
+            double lv[kNE];
+#pragma unroll
+            for (int i = 0; i < kNE; ++i) {
+                const int ei = eg + 64 * i;
+                lv[i] = ei < E ? (((resc[0][ei] + resc[1][ei]) + resc[2][ei]) + resc[3][ei]) + static_cast<double>(bl[i]) : 0.0;
+            }
+            double sv[kSel];
+            int se[kSel];
+            wave_topk(lv, eg, true, E, kk_sel, sv, se);
+            emit_token(lv, sv, se, eg, true, E, k, renorm, lane, idx + static_cast<size_t>(t) * k, w + static_cast<size_t>(t) * k);
+        }
+        __syncthreads();
     }
 }
 
 }  // namespace
 
+size_t route_scratch_bytes(const moe_cfg& c) {
+    if (c.dtype != MOE_BF16) return 0;
+    const size_t EP = static_cast<size_t>((c.E + 31) / 32) * 32;
+    return align256(EP * c.d * 2) + align256(static_cast<size_t>(c.d / 64) * EP * 4);
+}
+
 int launch_route(const moe_cfg& c, const void* x, const void* Wg, const float* bias, int32_t* idx, float* w,
-                 hipStream_t s) {
+                 void* scratch, hipStream_t s) {
     if (c.T == 0) return MOE_OK;
+    if (c.dtype == MOE_BF16) {
+        const int NB = (c.E + 31) / 32;
+        const size_t EP = static_cast<size_t>(NB) * 32;
+        uint4* pack = static_cast<uint4*>(scratch);
+        float* part = reinterpret_cast<float*>(static_cast<char*>(scratch) + align256(EP * c.d * 2));
+        hipLaunchKernelGGL(gate_prep_kernel, dim3(c.d / 64), dim3(256), 0, s, static_cast<const uint16_t*>(Wg), c.d, c.E, NB,
+                           pack, part);
+        MOE_LAUNCH_CHECK("gate_prep_kernel");
+        dim3 grid((c.T + kGateTokens - 1) / kGateTokens), block(256);
+#define MOE_ROUTE_CASE(N)                                                                                             \
+    case N:                                                                                                           \
+        hipLaunchKernelGGL(route_mfma_kernel<N>, grid, block, 0, s, static_cast<const uint16_t*>(x),                   \
+                           static_cast<const uint16_t*>(Wg), pack, part, bias, idx, w, c.T, c.d, c.E, c.k, c.renorm); \
+        break;
+        switch (NB) {
+            MOE_ROUTE_CASE(1) MOE_ROUTE_CASE(2) MOE_ROUTE_CASE(3) MOE_ROUTE_CASE(4)
+            MOE_ROUTE_CASE(5) MOE_ROUTE_CASE(6) MOE_ROUTE_CASE(7) MOE_ROUTE_CASE(8)
+            default: return fail(MOE_ERR_UNSUPPORTED, "E = %d is out of range", c.E);
+        }
+#undef MOE_ROUTE_CASE
+        MOE_LAUNCH_CHECK("route_mfma_kernel");
+        return MOE_OK;
+    }
     const int per_block = kWaves * kTPW;
     dim3 grid((c.T + per_block - 1) / per_block), block(kWaves * 64);
-    if (c.dtype == MOE_BF16)
-        hipLaunchKernelGGL(route_kernel<__bf16>, grid, block, 0, s, static_cast<const __bf16*>(x),
-                           static_cast<const __bf16*>(Wg), bias, idx, w, c.T, c.d, c.E, c.k, c.renorm);
-    else
-        hipLaunchKernelGGL(route_kernel<float>, grid, block, 0, s, static_cast<const float*>(x),
-                           static_cast<const float*>(Wg), bias, idx, w, c.T, c.d, c.E, c.k, c.renorm);
+    hipLaunchKernelGGL(route_kernel<float>, grid, block, 0, s, static_cast<const float*>(x),
+                       static_cast<const float*>(Wg), bias, idx, w, c.T, c.d, c.E, c.k, c.renorm);
     MOE_LAUNCH_CHECK("route_kernel");
     return MOE_OK;
 }
