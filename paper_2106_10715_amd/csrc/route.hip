@@ -394,36 +394,45 @@ __global__ __launch_bounds__(256) void route_mfma_kernel(const uint16_t* __restr
     }
     __syncthreads();
 
-    // ---- fp64 re-evaluation of the tokens that were too close to call, by the whole block:
-    // wave w sums rows [w d/4, (w+1) d/4), the four partial sums are added in wave order.
-    int EPl = 1;
-    while (EPl < E && EPl < 64) EPl <<= 1;
-    const int KS = 64 / EPl, eg2 = lane & (EPl - 1), ks = lane / EPl;
+    // ---- fp64 re-evaluation of the tokens that were too close to call, by the whole block, from the
+    // same packed fragments and with the same split as the MFMA pass: wave w takes the groups
+    // S = w, w+4, ..., lane (c, h) the 32 rows 64 S + 32 h .. of column c of every expert block; the two
+    // halves are added by a lane exchange, the four waves in wave order.
     for (int tt = 0; tt < kGateTokens; ++tt) {
         if (!flagged[tt]) continue;                                      // uniform for the block
         const int t = t0 + tt;
-        const uint16_t* xr = x + static_cast<size_t>(t) * d;
-        double a64[kNE];
+        const uint4* xr = reinterpret_cast<const uint4*>(x + static_cast<size_t>(t) * d + 32 * (lane >> 5));
+        double a64[NB];
 #pragma unroll
-        for (int i = 0; i < kNE; ++i) a64[i] = 0.0;
-        const int kend = (wave + 1) * (d / 4);
-        for (int kk = wave * (d / 4) + ks; kk < kend; kk += KS) {
-            const double xv = static_cast<double>(__uint_as_float(static_cast<uint32_t>(xr[kk]) << 16));
+        for (int nb = 0; nb < NB; ++nb) a64[nb] = 0.0;
+        for (int S = wave; S < nS; S += 4) {
+            uint4 xa[4];
 #pragma unroll
-            for (int i = 0; i < kNE; ++i) {
-                const int ei = eg2 + 64 * i;
-                if (ei < E)
-                    a64[i] = fma(xv, static_cast<double>(__uint_as_float(static_cast<uint32_t>(Wg[static_cast<size_t>(kk) * E + ei]) << 16)),
-                                 a64[i]);
+            for (int q = 0; q < 4; ++q) xa[q] = xr[S * 8 + q];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const uint4* bp = pack + ((static_cast<size_t>(nb) * nS + S) * 4) * 64 + lane;
+                uint4 wb[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) wb[q] = bp[q * 64];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t xu[4] = {xa[q].x, xa[q].y, xa[q].z, xa[q].w};
+                    const uint32_t wu[4] = {wb[q].x, wb[q].y, wb[q].z, wb[q].w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        a64[nb] = fma(static_cast<double>(__uint_as_float(xu[i] << 16)),
+                                      static_cast<double>(__uint_as_float(wu[i] << 16)), a64[nb]);
+                        a64[nb] = fma(static_cast<double>(__uint_as_float(xu[i] & 0xffff0000u)),
+                                      static_cast<double>(__uint_as_float(wu[i] & 0xffff0000u)), a64[nb]);
+                    }
+                }
             }
         }
-        for (int off = EPl; off < 64; off <<= 1)
 #pragma unroll
-            for (int i = 0; i < kNE; ++i) a64[i] += __shfl_xor(a64[i], off);
-        if (ks == 0) {
-#pragma unroll
-            for (int i = 0; i < kNE; ++i)
-                if (eg2 + 64 * i < E) resc[wave][eg2 + 64 * i] = a64[i];
+        for (int nb = 0; nb < NB; ++nb) {
+            a64[nb] += __shfl_xor(a64[nb], 32);
+            if (lane < 32) resc[wave][32 * nb + lane] = a64[nb];
         }
         __syncthreads();
         if (wave == 0) {
