@@ -151,21 +151,27 @@ template <int IMM>
 __device__ inline void ld_pinned(u32x4& dst, uint32_t voff, const void* sbase) {
     asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3" : "=v"(dst) : "v"(voff), "s"(sbase), "n"(IMM) : "memory");
 }
+// Same, marked non-temporal: the weights are read once, they should not push the activation tiles
+// (which every column group of an expert re-reads) out of the L2.
+template <int IMM>
+__device__ inline void ld_pinned_stream(u32x4& dst, uint32_t voff, const void* sbase) {
+    asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3 nt" : "=v"(dst) : "v"(voff), "s"(sbase), "n"(IMM) : "memory");
+}
 
 // The two fragments of one (column unit, k-step) are adjacent in the packed block:
 // [k-step][2][64 lanes] x 16 bytes (2 KiB per k-step); a wave with NF = 1 reads one of the two.
 // voff = byte offset of this lane inside its wave's stream at the first k-step of the pipeline step.
 template <int NF>
 __device__ inline void load_b(BFrags<NF>& b, uint32_t voff, const void* wave_base) {
-    ld_pinned<0>(b.v[0][0], voff, wave_base);
-    if (NF == 2) ld_pinned<1024>(b.v[0][NF - 1], voff, wave_base);
-    ld_pinned<2048>(b.v[1][0], voff, wave_base);
-    if (NF == 2) ld_pinned<3072>(b.v[1][NF - 1], voff, wave_base);
+    ld_pinned_stream<0>(b.v[0][0], voff, wave_base);
+    if (NF == 2) ld_pinned_stream<1024>(b.v[0][NF - 1], voff, wave_base);
+    ld_pinned_stream<2048>(b.v[1][0], voff, wave_base);
+    if (NF == 2) ld_pinned_stream<3072>(b.v[1][NF - 1], voff, wave_base);
     const uint32_t voff2 = voff + 4096;
-    ld_pinned<0>(b.v[2][0], voff2, wave_base);
-    if (NF == 2) ld_pinned<1024>(b.v[2][NF - 1], voff2, wave_base);
-    ld_pinned<2048>(b.v[3][0], voff2, wave_base);
-    if (NF == 2) ld_pinned<3072>(b.v[3][NF - 1], voff2, wave_base);
+    ld_pinned_stream<0>(b.v[2][0], voff2, wave_base);
+    if (NF == 2) ld_pinned_stream<1024>(b.v[2][NF - 1], voff2, wave_base);
+    ld_pinned_stream<2048>(b.v[3][0], voff2, wave_base);
+    if (NF == 2) ld_pinned_stream<3072>(b.v[3][NF - 1], voff2, wave_base);
 }
 
 // End-of-step wait: at most 4*NF loads (this step's weight prefetch) may still be outstanding.
@@ -355,7 +361,9 @@ __global__ __launch_bounds__(256) void ffn_mfma_kernel(const uint16_t* __restric
     const uint32_t wb_lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(wbi))));
     const uint32_t wb_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(wbi >> 32))));
     const void* wave_w = reinterpret_cast<const void*>((static_cast<uintptr_t>(wb_hi) << 32) | static_cast<uintptr_t>(wb_lo));
-    const unsigned col_group = (GATED || NF == 2) ? blockIdx.y : (blockIdx.y >> 1);   // same for both unit widths
+    // column groups are taken eight at a time: the blocks of one expert that run together then read the
+    // same activation lines at the same time (one L2 miss instead of eight)
+    const unsigned col_group = ((GATED || NF == 2) ? blockIdx.y : (blockIdx.y >> 1)) >> 3;   // same for both unit widths
     const unsigned key = static_cast<unsigned>(e) * 37u + static_cast<unsigned>(row_begin - offsets[e]) / kTileM * 11u +
                          col_group * 17u;
     switch ((rows + 31) >> 5) {
