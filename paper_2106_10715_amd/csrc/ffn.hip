@@ -28,6 +28,18 @@ __device__ inline float act_fn(float z, int act) {
     return 0.5f * z * (1.0f + tanhf(u));
 }
 
+// Activation for results that are rounded to bf16 right away: erf from the rational-times-Gaussian
+// approximation 7.1.26 of Abramowitz & Stegun (|error| <= 1.5e-7 on erf, 5e-7 on GELU, three orders
+// below the bf16 rounding of the result) instead of the library erff, which is several times longer.
+__device__ inline float act_fn_bf16(float z, int act) {
+    if (act != 0) return act_fn(z, act);
+    const float x = fabsf(z) * 0.70710678118654752f;
+    const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * x);
+    const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+    const float erf_abs = 1.0f - poly * __expf(-x * x);
+    return 0.5f * z * (1.0f + copysignf(erf_abs, z));
+}
+
 // Which (expert, row tile) a block works on: tile slot `slot` counted over the experts
 // [e_first, e_first + e_count) in order, tile_m rows per tile.  Returns false when the slot is past
 // the last tile (uniform for the block).  Must be called by all threads of the block.
@@ -315,7 +327,7 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
             if (r < rows) {
                 uint16_t* crow = C + static_cast<size_t>(row_begin + r) * N;
                 if (GATED) {
-                    const float h = act_fn(acc[mb][0][v], act) * acc[mb][1][v];
+                    const float h = act_fn_bf16(acc[mb][0][v], act) * acc[mb][1][v];
                     crow[unit * 32 + col_in] = __builtin_bit_cast(uint16_t, static_cast<__bf16>(h));
                 } else {
 #pragma unroll
