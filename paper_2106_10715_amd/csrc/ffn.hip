@@ -315,26 +315,47 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
             for (int j = 0; j < NF; ++j) asm volatile("" : : "v"(ring[r].v[ks][j]));
 #pragma unroll
     for (int mb = 0; mb < MBS; ++mb) asm volatile("" : : "v"(areg.v[mb]));
-    if (!active) return;
-
-    // accumulator layout of the 32x32 MFMA: lane holds column lane%32, rows 8*(v/4) + 4*(lane/32) + v%4
+    // Epilogue through LDS (the activation buffers are free now): every wave applies the activation to
+    // its accumulators and writes bf16 values into a row-major tile of the block's columns; then the
+    // whole block stores that tile with 16 bytes per lane, whole 64-byte segments per row.  All rows
+    // are computed (clamped duplicates give finite values), only real rows are stored.
+    constexpr int W = 32 * (GATED ? 1 : NF);            // output columns per wave
+    constexpr int kTileRowBytes = 4 * W * 2 + 16;       // padded: the two row groups of a wave hit different banks
+    constexpr int kRowsPerPass = W == 32 ? 256 : 128;   // tile rows that fit the LDS
+    constexpr int kLanesPerRow = W / 2;                 // 16-byte stores per tile row
+    constexpr int kRowsPerIter = 256 / kLanesPerRow;
+    char* tile = reinterpret_cast<char*>(&lds[0][0]);
+    static_assert(kRowsPerPass * kTileRowBytes <= static_cast<int>(sizeof(lds)), "epilogue tile must fit the LDS buffers");
+    const int wave = threadIdx.x >> 6;
     const int col_in = lane & 31, row_in = 4 * (lane >> 5);
 #pragma unroll
-    for (int mb = 0; mb < MBS; ++mb) {
+    for (int p0 = 0; p0 < MBS * 32; p0 += kRowsPerPass) {
+        if (p0 > 0) __syncthreads();                    // the previous pass has been stored
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int r = mb * 32 + 8 * (v >> 2) + row_in + (v & 3);
-            if (r < rows) {
-                uint16_t* crow = C + static_cast<size_t>(row_begin + r) * N;
+        for (int mb = p0 / 32; mb < MBS && mb < (p0 + kRowsPerPass) / 32; ++mb) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                // accumulator layout of the 32x32 MFMA: lane holds column lane%32, rows 8*(v/4) + 4*(lane/32) + v%4
+                const int r = mb * 32 + 8 * (v >> 2) + row_in + (v & 3) - p0;
+                uint16_t* trow = reinterpret_cast<uint16_t*>(tile + r * kTileRowBytes) + wave * W + col_in;
                 if (GATED) {
                     const float h = act_fn_bf16(acc[mb][0][v], act) * acc[mb][1][v];
-                    crow[unit * 32 + col_in] = __builtin_bit_cast(uint16_t, static_cast<__bf16>(h));
+                    trow[0] = __builtin_bit_cast(uint16_t, static_cast<__bf16>(h));
                 } else {
 #pragma unroll
-                    for (int j = 0; j < NF; ++j)
-                        crow[unit * 32 * NF + 32 * j + col_in] =
-                            __builtin_bit_cast(uint16_t, static_cast<__bf16>(acc[mb][j][v]));
+                    for (int j = 0; j < NF; ++j) trow[32 * j] = __builtin_bit_cast(uint16_t, static_cast<__bf16>(acc[mb][j][v]));
                 }
+            }
+        }
+        __syncthreads();
+        const int seg = (threadIdx.x % kLanesPerRow) * 8;       // first of this lane's 8 columns inside the block
+        const int src_wave = seg / W;
+        const int out_unit = unit - wave + src_wave;            // unit of the wave that produced them
+        if (out_unit < N / W) {
+            uint16_t* cbase = C + static_cast<size_t>(out_unit) * W + (seg % W);
+            for (int r = threadIdx.x / kLanesPerRow; r < kRowsPerPass && p0 + r < rows; r += kRowsPerIter) {
+                const uint4 val = *reinterpret_cast<const uint4*>(tile + r * kTileRowBytes + seg * 2);
+                *reinterpret_cast<uint4*>(cbase + static_cast<size_t>(row_begin + p0 + r) * N) = val;
             }
         }
     }
