@@ -363,7 +363,7 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
 
 // C[rows of one expert tile, N] = A[rows, K] * B_e, B_e in packed fragment order.
 // A block is up to 256 rows of one expert (only the 32-row blocks that hold rows are computed) by
-// 4 waves; wave w owns column unit blockIdx.y*4 + w for all rows.
+// 4 waves; wave w owns column unit 4*(column group) + w for all rows.
 // GATED (NF = 2): a unit is 32 output columns whose two fragments per k-step are (W_gate, W_in); the
 //   epilogue writes act(gate) * in.
 // otherwise a unit is 32 * NF output columns of W_out.
@@ -373,14 +373,27 @@ template <bool GATED, int NF>
 __global__ __launch_bounds__(256) void ffn_mfma_kernel(const uint16_t* __restrict__ A, const int32_t* __restrict__ offsets,
                                                        int e_first, int e_count, const char* __restrict__ W,
                                                        size_t expert_stride_bytes, size_t block_offset_bytes,
-                                                       uint16_t* __restrict__ C, int K, int N, int act) {
+                                                       uint16_t* __restrict__ C, int K, int N, int act, int y_chunks,
+                                                       int mt_shift) {
     __shared__ uint4 lds[2][kTileM * kLdsRow];     // 2 x 36 KiB activation tiles, padded rows
+    // Block id -> (row-tile slot, column group).  Workgroups go round-robin to the 8 XCDs, each with its
+    // own L2, so the id is split into x = id % 8 (the XCD) and the position q in that XCD's queue; 32
+    // consecutive positions (about what an XCD runs at a time) are 2^mt_shift neighbouring row tiles x
+    // 32 / 2^mt_shift neighbouring column groups.  Tiles of one expert then share its weight stream, and
+    // the column groups of a tile share its activation tile, in that XCD's L2; the groups of tiles are
+    // dealt to the XCDs in turn so that the load is even (fewer tiles per group when there are few).
+    const unsigned xcd = blockIdx.x & 7u, q = blockIdx.x >> 3;
+    const unsigned ny = 32u >> mt_shift;           // column groups per run of 32; 1 << mt_shift row tiles
+    const unsigned yg = q & (ny - 1u), mt = (q / ny) & ((1u << mt_shift) - 1u), rest = q >> 5;
+    const unsigned y_chunk = rest % static_cast<unsigned>(y_chunks), tile_group = rest / static_cast<unsigned>(y_chunks);
+    const int slot = static_cast<int>((((tile_group << 3) + xcd) << mt_shift) + mt);
+    const int block_y = static_cast<int>(y_chunk * ny + yg);
     int e, row_begin, rows;
-    if (!find_tile(offsets, e_first, e_count, kTileM, blockIdx.x, e, row_begin, rows)) return;
+    if (!find_tile(offsets, e_first, e_count, kTileM, slot, e, row_begin, rows)) return;
 
     const int wave = threadIdx.x >> 6;
     const int units = N / (32 * (GATED ? 1 : NF));
-    const int unit = blockIdx.y * 4 + wave;
+    const int unit = block_y * 4 + wave;
     const bool active = unit < units;              // a wave past the last unit recomputes the last one, stores nothing
     const int u = active ? unit : units - 1;
     const int steps16 = K / 16;
@@ -394,11 +407,12 @@ __global__ __launch_bounds__(256) void ffn_mfma_kernel(const uint16_t* __restric
     const uint32_t wb_lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(wbi))));
     const uint32_t wb_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(wbi >> 32))));
     const void* wave_w = reinterpret_cast<const void*>((static_cast<uintptr_t>(wb_hi) << 32) | static_cast<uintptr_t>(wb_lo));
-    // column groups are taken eight at a time: the blocks of one expert that run together then read the
-    // same activation lines at the same time (one L2 miss instead of eight)
-    const unsigned col_group = ((GATED || NF == 2) ? blockIdx.y : (blockIdx.y >> 1)) >> 3;   // same for both unit widths
-    const unsigned key = static_cast<unsigned>(e) * 37u + static_cast<unsigned>(row_begin - offsets[e]) / kTileM * 11u +
-                         col_group * 17u;
+    if (block_y * 4 >= units) return;              // past the last column group (uniform for the block)
+    // The sweep over the reduction dimension starts at a step that depends on the expert and on the
+    // chunk of 8 column groups only: blocks that share a weight stream or an activation tile walk it
+    // together, other blocks are out of step with them.
+    const unsigned col_chunk = static_cast<unsigned>(block_y) >> ((GATED || NF == 2) ? 3 : 4);   // same for both unit widths
+    const unsigned key = static_cast<unsigned>(e) * 37u + col_chunk * 17u;
     switch ((rows + 31) >> 5) {
         case 1: ffn_tile<GATED, NF, 1>(lds, A, row_begin, rows, wave_w, C, K, N, unit, active, act, key); break;
         case 2: ffn_tile<GATED, NF, 2>(lds, A, row_begin, rows, wave_w, C, K, N, unit, active, act, key); break;
@@ -512,30 +526,40 @@ int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, 
     if (c.dtype == MOE_BF16) {
         // grid.x = row-tile slots (fastest varying, padded to the 8 XCDs so that the blocks sharing one
         // activation tile land on one XCD and its L2), grid.y = groups of 4 column units
+        // one-dimensional grid: 8 XCDs x (groups of 4 row-tile slots per XCD) x (chunks of 8 column groups) x 32
         long slots = max_rows / kTileM + e_count;
-        slots = (slots + 7) / 8 * 8;
-        if (slots > 0x7fffffffL) return fail(MOE_ERR_UNSUPPORTED, "too many row tiles for one launch (%ld)", slots);
+        const int mt_shift = slots >= 32 ? 2 : slots >= 16 ? 1 : 0;   // row tiles per group: 4, 2 or 1
+        const long tile_groups = (slots + (8L << mt_shift) - 1) / (8L << mt_shift);   // per XCD
+        auto grid_for = [&](int col_groups, int& y_chunks) {
+            const int ny = 32 >> mt_shift;
+            y_chunks = (col_groups + ny - 1) / ny;
+            return tile_groups * y_chunks * 32 * 8;
+        };
         const size_t down_off = 2 * df * 2;
         dim3 block(256);
-        dim3 grid_up(static_cast<unsigned>(slots), (c.f / 32 + 3) / 4);
-        hipLaunchKernelGGL((ffn_mfma_kernel<true, 2>), grid_up, block, 0, s, static_cast<const uint16_t*>(Xp), offsets,
-                           e_first, e_count, static_cast<const char*>(W), expert_stride_bytes, size_t(0),
-                           static_cast<uint16_t*>(H), c.d, c.f, c.act);
+        int yc = 0;
+        long blocks = grid_for((c.f / 32 + 3) / 4, yc);
+        if (blocks > 0x7fffffffL) return fail(MOE_ERR_UNSUPPORTED, "too many blocks for one launch (%ld)", blocks);
+        hipLaunchKernelGGL((ffn_mfma_kernel<true, 2>), dim3(static_cast<unsigned>(blocks)), block, 0, s,
+                           static_cast<const uint16_t*>(Xp), offsets, e_first, e_count, static_cast<const char*>(W),
+                           expert_stride_bytes, size_t(0), static_cast<uint16_t*>(H), c.d, c.f, c.act, yc, mt_shift);
         MOE_LAUNCH_CHECK("ffn_mfma_kernel<up>");
         if (between != nullptr) MOE_HIP_CHECK(hipEventRecord(between, s));
         // down-projection: narrow (32-column) units when wide ones would leave compute units idle
         const long tiles_hint = (max_rows + kTileM - 1) / kTileM > e_count ? (max_rows + kTileM - 1) / kTileM : e_count;
         const bool narrow = tiles_hint * ((c.d / 64 + 3) / 4) < 2 * 256;
         if (narrow) {
-            dim3 grid_dn(static_cast<unsigned>(slots), (c.d / 32 + 3) / 4);
-            hipLaunchKernelGGL((ffn_mfma_kernel<false, 1>), grid_dn, block, 0, s, static_cast<const uint16_t*>(H), offsets,
-                               e_first, e_count, static_cast<const char*>(W), expert_stride_bytes, down_off,
-                               static_cast<uint16_t*>(Yp), c.f, c.d, c.act);
+            blocks = grid_for((c.d / 32 + 3) / 4, yc);
+            if (blocks > 0x7fffffffL) return fail(MOE_ERR_UNSUPPORTED, "too many blocks for one launch (%ld)", blocks);
+            hipLaunchKernelGGL((ffn_mfma_kernel<false, 1>), dim3(static_cast<unsigned>(blocks)), block, 0, s,
+                               static_cast<const uint16_t*>(H), offsets, e_first, e_count, static_cast<const char*>(W),
+                               expert_stride_bytes, down_off, static_cast<uint16_t*>(Yp), c.f, c.d, c.act, yc, mt_shift);
         } else {
-            dim3 grid_dn(static_cast<unsigned>(slots), (c.d / 64 + 3) / 4);
-            hipLaunchKernelGGL((ffn_mfma_kernel<false, 2>), grid_dn, block, 0, s, static_cast<const uint16_t*>(H), offsets,
-                               e_first, e_count, static_cast<const char*>(W), expert_stride_bytes, down_off,
-                               static_cast<uint16_t*>(Yp), c.f, c.d, c.act);
+            blocks = grid_for((c.d / 64 + 3) / 4, yc);
+            if (blocks > 0x7fffffffL) return fail(MOE_ERR_UNSUPPORTED, "too many blocks for one launch (%ld)", blocks);
+            hipLaunchKernelGGL((ffn_mfma_kernel<false, 2>), dim3(static_cast<unsigned>(blocks)), block, 0, s,
+                               static_cast<const uint16_t*>(H), offsets, e_first, e_count, static_cast<const char*>(W),
+                               expert_stride_bytes, down_off, static_cast<uint16_t*>(Yp), c.f, c.d, c.act, yc, mt_shift);
         }
         MOE_LAUNCH_CHECK("ffn_mfma_kernel<down>");
         return MOE_OK;
