@@ -41,7 +41,7 @@ __device__ inline float act_fn_bf16(float z, int act) {
 }
 
 // Which (expert, row tile) a block works on: tile slot `slot` counted over the experts
-// [e_first, e_first + e_count) in order, tile_m rows per tile.  Returns false when the slot is past
+// [e_first, e_first + e_count) in order, at most tile_m rows per tile.  Returns false when the slot is past
 // the last tile (uniform for the block).  Must be called by all threads of the block.
 __device__ inline bool find_tile(const int32_t* __restrict__ offsets, int e_first, int e_count, int tile_m, int slot,
                                  int& e_out, int& row_begin, int& rows) {
@@ -77,8 +77,13 @@ __device__ inline bool find_tile(const int32_t* __restrict__ offsets, int e_firs
     __syncthreads();
     if (sh_e < 0) return false;
     e_out = e_first + sh_e;
-    row_begin = offsets[e_out] + sh_mt * tile_m;
-    rows = min(tile_m, offsets[e_out + 1] - row_begin);
+    // the expert's rows are split evenly over its tiles (in multiples of 32 rows), not into full tiles
+    // and a small remainder: equal tiles finish together and none is nearly empty
+    const int n = offsets[e_out + 1] - offsets[e_out];
+    const int tiles = (n + tile_m - 1) / tile_m;
+    const int per_tile = min(tile_m, ((n + tiles - 1) / tiles + 31) & ~31);
+    row_begin = offsets[e_out] + sh_mt * per_tile;
+    rows = min(per_tile, offsets[e_out + 1] - row_begin);
     return true;
 }
 
