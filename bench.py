@@ -38,6 +38,23 @@ def parse():
     return ap.parse_args()
 
 
+def measured_traffic(workload: str, which: str):
+    """HBM bytes per launch of an expert FFN kernel as the FETCH_SIZE / WRITE_SIZE counters of rocprofv3
+    gave them (table written next to the library from the counter runs summarised under profiles/), or
+    None when there is no figure for this workload or the kernel source has changed since."""
+    import hashlib
+    pkg = os.path.join(ROOT, "paper_2106_10715_amd")
+    try:
+        tab = json.load(open(os.path.join(pkg, "ffn_traffic.json")))
+        sha = hashlib.sha256(open(os.path.join(pkg, "csrc", "ffn.hip"), "rb").read()).hexdigest()
+    except OSError:
+        return None
+    if tab.get("source_sha256") != sha or workload not in tab:
+        return None
+    t = tab[workload][which]
+    return {"read_bytes": t["read_bytes"], "write_bytes": t["write_bytes"], "bytes": t["read_bytes"] + t["write_bytes"]}
+
+
 def cpu_baseline(wl, counts, offsets, perm):
     """The oracle as it stands, timed on the host cores on a bounded sample: routing and batching of
     the whole batch, then the expert FFN of the first experts' complete segments until about
@@ -173,22 +190,26 @@ def main():
         per_call = M.moe_stage_timing_read(args.steps)
         M.moe_stage_timing_disable()
         stage_ms = {s: float(np.mean([c[s] for c in per_call])) for s in M.STAGES}
-        up_bytes = live * 2 * d * f * es + A * d * es        # W_gate+W_in of every non-empty expert once, Xp once
-        down_bytes = live * d * f * es + A * d * es          # W_out once, Yp once
+        # Algorithmic bytes: W_gate+W_in of every non-empty expert once and Xp once for the up kernel, W_out once
+        # and Yp once for the down kernel.  H[A,f] goes through HBM between the two (written by up, read by
+        # down): traffic of this implementation, reported separately and not counted as algorithmic.
+        up_bytes = live * 2 * d * f * es + A * d * es
+        down_bytes = live * d * f * es + A * d * es
         up_gbs = up_bytes / (stage_ms["ffn_up"] * 1e-3) / 1e9
         up_tflops = 4.0 * d * f * A / (stage_ms["ffn_up"] * 1e-3) / 1e12
         # the up kernel is bound by whichever roofline gives the longer time for this workload
         t_hbm = up_bytes / (HBM_PEAK_GBS * 1e9)
         t_mfma = 4.0 * d * f * A / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+        traffic = measured_traffic(args.workload, "up")
         if t_hbm >= t_mfma:
             roof = {"bound": "hbm", "achieved": up_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": up_gbs / HBM_PEAK_GBS, "traffic": None}
+                    "frac": up_gbs / HBM_PEAK_GBS, "traffic": traffic}
         else:
             roof = {"bound": "mfma", "achieved": up_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": up_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+                    "frac": up_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic}
         roof.update({"kernel": "ffn_mfma_kernel<true> (expert up-projection, gate/in fused)",
                      "avg_launch_ms": stage_ms["ffn_up"], "algorithmic_bytes_per_launch": up_bytes,
-                     "algorithmic_flops_per_launch": 4.0 * d * f * A})
+                     "algorithmic_flops_per_launch": 4.0 * d * f * A, "h_staging_bytes_per_launch": A * f * es})
         out["roofline"] = roof
         ffn_ms = stage_ms["ffn_up"] + stage_ms["ffn_down"]
         out["stages_ms"] = stage_ms
