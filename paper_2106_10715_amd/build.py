@@ -25,22 +25,39 @@ def _hipcc() -> str:
 
 # ffn.hip spells out its software pipeline (loads first, LDS reads one k-step ahead of the MFMAs); the
 # machine scheduler would fold that back into load-use pairs to save registers, so it is switched off there.
-EXTRA = {"ffn.hip": ["-mllvm", "-enable-misched=false", "-Rpass-analysis=kernel-resource-usage"]}
-# The MFMA kernels of ffn.hip keep loads in flight in registers the compiler knows nothing about; a
-# register spill there could save such a register before its load has landed.  The build refuses it.
-NO_SPILL = {"ffn.hip": "ffn_mfma_kernel"}
+EXTRA = {"ffn.hip": ["-mllvm", "-enable-misched=false"]}
+# The MFMA kernels of ffn.hip keep loads in flight in registers the compiler knows nothing about and count
+# the outstanding loads by hand.  Spill code inside such a region could save a register before its load
+# has landed, and its own memory operations would be counted as if they were the kernel's.  The source
+# brackets those regions with "; pipeline begin" / "; pipeline end"; the build reads the assembly and
+# refuses any scratch access between the two or inside an inner loop of these kernels.
+NO_SPILL = {"ffn.hip": "ffn_mfma"}
 
 
-def _check_no_spill(src: str, remarks: str) -> None:
-    current = ""
-    for line in remarks.splitlines():
-        if "Function Name:" in line:
-            current = line.split("Function Name:")[1].strip()
-        elif NO_SPILL[src] in current and ("VGPRs Spill:" in line or "SGPRs Spill:" in line):
-            n = int(line.split("Spill:")[1].split()[0])
-            if n != 0:
-                raise RuntimeError(f"{src}: {current} spills {n} registers ({line.strip()}); "
-                                   "the hand-counted load waits of this kernel do not allow that")
+def check_no_spill(asm: str, kernel_pattern: str, what: str = "assembly") -> None:
+    """Raises if a kernel whose name contains kernel_pattern touches scratch memory between a
+    "; pipeline begin" and the next "; pipeline end", or inside a loop nested in another loop."""
+    kernel, inside, inner = None, False, False
+    lines = asm.splitlines()
+    for n, line in enumerate(lines, 1):
+        text = line.strip()
+        if line.startswith("_Z") and ":" in line:                       # a function starts
+            name = line.split(":")[0]
+            kernel = name if kernel_pattern in name else None
+            inside = inner = False
+        elif text.startswith(".end_amdhsa_kernel") or text.startswith(".Lfunc_end"):
+            kernel = None
+        if kernel is None:
+            continue
+        if line.startswith(".LBB") or line.startswith("; %bb."):        # a block: which loop is it in?
+            note = line + (lines[n] if n < len(lines) and lines[n].strip().startswith(";") else "")
+            inner = "Depth=2" in note or "Depth=3" in note
+        if "; pipeline begin" in text:
+            inside = True
+        elif "; pipeline end" in text:
+            inside = False
+        elif text.startswith("scratch_") and (inside or inner):
+            raise RuntimeError(f"{what}: spill code inside a hand-counted load pipeline of {kernel} (line {n}: {text})")
 
 
 def _compile(src: str) -> str:
@@ -49,17 +66,13 @@ def _compile(src: str) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     if r.returncode == 0 and src in NO_SPILL:
-        _check_no_spill(src, r.stderr)
-    kept, skip = [], 0
-    for l in r.stderr.splitlines():
-        if "-Rpass-analysis=kernel-resource-usage" in l:
-            skip = 2                                # a remark is followed by the source line and a caret line
-        elif skip and (l.lstrip()[:1].isdigit() or l.lstrip().startswith("|")):
-            skip -= 1
-        elif noise not in l:
-            kept.append(l)
-            skip = 0
-    err = "\n".join(kept)
+        asm = os.path.join(HERE, "_build", src.replace(".hip", ".s"))
+        ra = subprocess.run([_hipcc(), *FLAGS, *EXTRA.get(src, []), "-S", "--cuda-device-only",
+                             os.path.join(CSRC, src), "-o", asm], capture_output=True, text=True)
+        if ra.returncode != 0:
+            raise RuntimeError(f"hipcc -S failed on {src}:\n{ra.stderr}")
+        check_no_spill(open(asm).read(), NO_SPILL[src], src)
+    err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{err}")
     if err.strip():

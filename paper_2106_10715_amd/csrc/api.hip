@@ -56,6 +56,7 @@ WsLayout ws_layout(const moe_cfg& c) {
     L.inv = take(A * 4);
     L.chunk_hist = take((chunks > 0 ? chunks : 1) * c.E * 4);
     L.route = take(route_scratch_bytes(c));
+    L.ffn_plan = take(ffn_plan_bytes(c));
     L.total = at > 0 ? at : 256;
     return L;
 }
@@ -159,7 +160,8 @@ int moe_expert_ffn(const moe_cfg* cfg, const void* Xp, const int32_t* offsets, c
     size_t eb = 0;
     moe_expert_bytes(cfg, &eb);
     return launch_expert_ffn(*cfg, Xp, offsets, 0, cfg->E, W_packed, eb, static_cast<long>(cfg->T) * cfg->k,
-                             static_cast<char*>(ws) + L.H, Yp, static_cast<hipStream_t>(stream));
+                             static_cast<char*>(ws) + L.H, Yp,
+                             reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.ffn_plan), static_cast<hipStream_t>(stream));
 }
 
 int moe_combine(const moe_cfg* cfg, const void* Yp, const int32_t* inv, const float* w, void* y, void* stream) {
@@ -208,8 +210,8 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
     if (tev) MOE_HIP_CHECK(hipEventRecord(tev[2], s));
 
     if (sctx == nullptr) {
-        if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, 0, c.E, W_packed, eb, A, base + L.H, base + L.Yp, s,
-                                       tev ? tev[3] : nullptr))
+        if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, 0, c.E, W_packed, eb, A, base + L.H, base + L.Yp,
+                                       reinterpret_cast<int32_t*>(base + L.ffn_plan), s, tev ? tev[3] : nullptr))
             return rc;
         if (tev) MOE_HIP_CHECK(hipEventRecord(tev[4], s));
     } else {
@@ -229,7 +231,8 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
                                          sctx->copy_stream));
             MOE_HIP_CHECK(hipEventRecord(sctx->loaded[slot], sctx->copy_stream));
             MOE_HIP_CHECK(hipStreamWaitEvent(s, sctx->loaded[slot], 0));
-            if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, e, 1, dst, eb, n_e, base + L.H, base + L.Yp, s))
+            if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, e, 1, dst, eb, n_e, base + L.H, base + L.Yp,
+                                           reinterpret_cast<int32_t*>(base + L.ffn_plan), s))
                 return rc;
             MOE_HIP_CHECK(hipEventRecord(sctx->released[slot], s));
             sctx->released_valid[slot] = true;

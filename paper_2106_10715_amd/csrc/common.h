@@ -51,6 +51,7 @@ struct WsLayout {
     size_t inv;        // [A] int32
     size_t chunk_hist; // [chunks, E] int32: per-chunk expert histograms, then per-chunk bases
     size_t route;      // gate projection in MFMA fragment order + per-group column sums of squares
+    size_t ffn_plan;   // work list and work counters of the expert FFN kernels
     size_t total;
 };
 WsLayout ws_layout(const moe_cfg& c);
@@ -68,8 +69,11 @@ int launch_pack(const moe_cfg& c, const void* Win, const void* Wgate, const void
 // (it sizes the grid; blocks past the real row count exit).
 // `between`, if not null, is recorded on `s` after the up kernel and before the down kernel.
 int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, int e_first, int e_count,
-                      const void* W, size_t expert_stride_bytes, long max_rows, void* H, void* Yp, hipStream_t s,
-                      hipEvent_t between = nullptr);
+                      const void* W, size_t expert_stride_bytes, long max_rows, void* H, void* Yp, int32_t* plan,
+                      hipStream_t s, hipEvent_t between = nullptr);
+// `plan`: ffn_plan_bytes(c) bytes of workspace, rewritten by every launch_expert_ffn (room for ffn_plan_tiles(c) row tiles).
+size_t ffn_plan_tiles(const moe_cfg& c);
+size_t ffn_plan_bytes(const moe_cfg& c);
 int launch_combine(const moe_cfg& c, const void* Yp, const int32_t* inv, const float* w, void* y, hipStream_t s);
 
 }  // namespace moe

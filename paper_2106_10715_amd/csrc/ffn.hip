@@ -150,7 +150,6 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint16_t* __restri
 // can be moved above it.
 
 constexpr int kKS = kKC / 16;           // MFMA k-steps per pipeline step
-constexpr int kRing = 3;                // weight-fragment register buffers
 constexpr int kLdsRow = 9;              // uint4 per activation row in LDS: 128 B of data + 16 B pad (conflict-free)
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -191,51 +190,118 @@ __device__ inline void load_b(BFrags<NF>& b, uint32_t voff, const void* wave_bas
     if (NF == 2) ld_pinned_stream<3072>(b.v[3][NF - 1], voff2, wave_base);
 }
 
-// End-of-step wait: at most 4*NF loads (this step's weight prefetch) may still be outstanding.
-template <int NF, int MBS>
-__device__ inline void wait_step(ARegs<MBS>& a, BFrags<NF>& next) {
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(kKS * NF) : "memory");
+// Wait until at most N_YOUNGER loads are outstanding; the registers named become usable afterwards.
+template <int N_YOUNGER, int NF, int MBS>
+__device__ inline void wait_loads(ARegs<MBS>& a, BFrags<NF>& b) {
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N_YOUNGER) : "memory");
 #pragma unroll
     for (int mb = 0; mb < MBS; ++mb) asm volatile("" : "+v"(a.v[mb]));
 #pragma unroll
     for (int ks = 0; ks < kKS; ++ks)
 #pragma unroll
-        for (int j = 0; j < NF; ++j) asm volatile("" : "+v"(next.v[ks][j]));
+        for (int j = 0; j < NF; ++j) asm volatile("" : "+v"(b.v[ks][j]));
 }
-
 // The activation tile lives in LDS row-major, one padded row of kLdsRow uint4 per tile row.
 // Staging: thread t moves, for i < MBS, the 16-byte piece (row i*32 + t/8, piece t%8): eight
 // neighbouring lanes fetch one whole 128-byte line of a row, and write 128 contiguous bytes of LDS.
 template <int MBS>
-__device__ inline void store_a(const ARegs<MBS>& a, uint4* lds_buf) {
-    u32x4* p = reinterpret_cast<u32x4*>(lds_buf) + (threadIdx.x >> 3) * kLdsRow + (threadIdx.x & 7);
+__device__ inline void store_a(const ARegs<MBS>& a, uint4* lds_buf, unsigned tid) {
+    u32x4* p = reinterpret_cast<u32x4*>(lds_buf) + (tid >> 3) * kLdsRow + (tid & 7);
 #pragma unroll
     for (int mb = 0; mb < MBS; ++mb) p[mb * 32 * kLdsRow] = a.v[mb];
 }
 
-// One pipeline step: 4 k-steps of MBS x NF MFMAs.  The A fragments of the next k-step are read from
-// LDS while the MFMAs of the current one run.  Fragment (mb, ks) of lane l = row mb*32 + l%32,
-// 8 elements at k = 16 ks + 8 (l / 32).
-template <int NF, int MBS>
-__device__ inline void mma_step(f32x16 (&acc)[MBS][NF], const uint4* lds_buf, const BFrags<NF>& b, int lane) {
-    const uint4* rp = lds_buf + (lane & 31) * kLdsRow + (lane >> 5);
-    uint4 af[2][MBS];
+// The MFMAs of a pipeline step are issued in units: unit u = (k-step u / H, row-block group u % H),
+// H = 1 or 2 groups of at most 4 row blocks.  The A fragments of unit u+1 are read from LDS while the
+// MFMAs of unit u run; two register buffers of G fragments alternate.
+// Fragment (mb, ks) of lane l = row mb*32 + l%32, 8 elements at k = 16 ks + 8 (l / 32).
+template <int MBS>
+struct Units {
+    static constexpr int H = MBS > 4 ? 2 : 1;
+    static constexpr int G = (MBS + H - 1) / H;
+    static constexpr int U = kKS * H;
+};
+
+template <int MBS, int UNIT>
+__device__ inline void read_unit(uint4 (&af)[Units<MBS>::G], const uint4* lds_buf, int lane) {
+    constexpr int ks = UNIT / Units<MBS>::H, mb0 = (UNIT % Units<MBS>::H) * Units<MBS>::G;
+    const uint4* rp = lds_buf + (lane & 31) * kLdsRow + (lane >> 5) + 2 * ks;
 #pragma unroll
-    for (int mb = 0; mb < MBS; ++mb) af[0][mb] = rp[mb * 32 * kLdsRow];
+    for (int i = 0; i < Units<MBS>::G; ++i)
+        if (mb0 + i < MBS) af[i] = rp[(mb0 + i) * 32 * kLdsRow];
+}
+
+template <int NF, int MBS, int UNIT>
+__device__ inline void mma_unit(f32x16 (&acc)[MBS][NF], const uint4 (&af)[Units<MBS>::G], const BFrags<NF>& b) {
+    constexpr int ks = UNIT / Units<MBS>::H, mb0 = (UNIT % Units<MBS>::H) * Units<MBS>::G;
 #pragma unroll
-    for (int ks = 0; ks < kKS; ++ks) {
-        if (ks + 1 < kKS) {
-#pragma unroll
-            for (int mb = 0; mb < MBS; ++mb) af[(ks + 1) & 1][mb] = rp[mb * 32 * kLdsRow + 2 * (ks + 1)];
-        }
-#pragma unroll
-        for (int mb = 0; mb < MBS; ++mb) {
+    for (int i = 0; i < Units<MBS>::G; ++i) {
+        if (mb0 + i < MBS) {
 #pragma unroll
             for (int j = 0; j < NF; ++j)
-                acc[mb][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af[ks & 1][mb]), as_bf16x8(b.v[ks][j]),
-                                                                     acc[mb][j], 0, 0, 0);
+                acc[mb0 + i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af[i]), as_bf16x8(b.v[ks][j]),
+                                                                          acc[mb0 + i][j], 0, 0, 0);
         }
     }
+}
+
+// One pipeline step.  Entering, af[0] holds the fragments of unit 0 of this step; leaving, those of
+// unit 0 of the next step.
+//   cur, nxt : LDS buffers of this and of the next step
+//   b        : weight fragments of this step
+//   a_next, b_next : registers of the next step's activations and weights (loads in flight); after the
+//              MFMAs of unit STAGE_AFTER at most N_YOUNGER younger loads may be outstanding, which
+//              means both have landed, and the activations are staged into nxt
+// The barrier sits before the MFMAs of the last unit: by then every fragment of this step has been
+// requested from cur and nxt is written, so the first fragments of the next step are fetched under
+// the last MFMAs instead of after them.
+template <int STAGE_AFTER, int N_YOUNGER, int NF, int MBS>
+__device__ inline void run_step(f32x16 (&acc)[MBS][NF], uint4 (&af)[2][Units<MBS>::G], const uint4* cur, uint4* nxt,
+                                const BFrags<NF>& b, ARegs<MBS>& a_next, BFrags<NF>& b_next, int lane, unsigned tid) {
+    constexpr int U = Units<MBS>::U;
+    static_assert(STAGE_AFTER < U - 1, "staging must precede the barrier");
+#define FFN_UNIT(UU)                                                                                   \
+    if constexpr ((UU) < U) {                                                                          \
+        if constexpr ((UU) + 1 < U) read_unit<MBS, (UU) + 1>(af[((UU) + 1) & 1], cur, lane);           \
+        if constexpr ((UU) + 1 == U) {                                                                 \
+            __syncthreads();                                                                           \
+            read_unit<MBS, 0>(af[0], nxt, lane);                                                       \
+        }                                                                                              \
+        mma_unit<NF, MBS, (UU)>(acc, af[(UU) & 1], b);                                                 \
+        if constexpr ((UU) == STAGE_AFTER) {                                                           \
+            wait_loads<N_YOUNGER>(a_next, b_next);                                                     \
+            store_a(a_next, nxt, tid);                                                                    \
+        }                                                                                              \
+    }
+    FFN_UNIT(0) FFN_UNIT(1) FFN_UNIT(2) FFN_UNIT(3) FFN_UNIT(4) FFN_UNIT(5) FFN_UNIT(6) FFN_UNIT(7)
+#undef FFN_UNIT
+}
+
+// A step without any overlap, for the few steps that do not fill a group of the unrolled pipeline:
+// fetch, wait, stage, compute.  Uses LDS buffer 0 and the registers passed in; nothing stays in flight.
+template <int NF, int MBS>
+__device__ inline void slow_step(f32x16 (&acc)[MBS][NF], uint4 (&af)[2][Units<MBS>::G], uint4* buf, ARegs<MBS>& a,
+                                 BFrags<NF>& b, int lane, unsigned tid) {
+    wait_loads<0>(a, b);
+    __syncthreads();                            // nobody reads buf any more
+    store_a(a, buf, tid);
+    __syncthreads();
+#define FFN_UNIT(UU)                                                          \
+    if constexpr ((UU) < Units<MBS>::U) {                                     \
+        read_unit<MBS, (UU)>(af[0], buf, lane);                               \
+        mma_unit<NF, MBS, (UU)>(acc, af[0], b);                               \
+    }
+    FFN_UNIT(0) FFN_UNIT(1) FFN_UNIT(2) FFN_UNIT(3) FFN_UNIT(4) FFN_UNIT(5) FFN_UNIT(6) FFN_UNIT(7)
+#undef FFN_UNIT
+}
+
+// The id of this thread inside its block, rebuilt from the wave number (which sits in a scalar
+// register) and the lane number, by instructions the compiler can neither hoist nor keep alive: a
+// vector register that holds the id across the main loop is one the loop does not have.
+__device__ inline unsigned thread_id(int wave) {
+    unsigned lane;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane));
+    return static_cast<unsigned>(wave) * 64u + lane;
 }
 
 // One tile of MBS 32-row blocks: the whole reduction loop and the epilogue.
@@ -246,80 +312,120 @@ __device__ inline void mma_step(f32x16 (&acc)[MBS][NF], const uint4* lds_buf, co
 template <bool GATED, int NF, int MBS>
 __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_t* __restrict__ A, int row_begin, int rows,
                                 const void* wave_base, uint16_t* __restrict__ C, int K, int N, int unit,
-                                bool active, int act, unsigned phase_key) {
-    const int lane = threadIdx.x & 63;
+                                bool active, int act, unsigned phase_key, int wave_s) {
+    unsigned tid = thread_id(wave_s);
+    const int lane = tid & 63;
+    // every tile height gets its own copy of the loop bounds: shared ones would be computed once for all
+    // heights and stay in registers across this one
+    asm volatile("" : "+s"(K), "+s"(N), "+s"(phase_key));
     const int chunks = K / kKC, last = chunks - 1;
 
-    // this thread's activation sources (byte offsets from A): row mb*32 + t/8 of every block, piece t%8;
-    // rows past the tile end re-read the last row
-    const int r0 = threadIdx.x >> 3;
-    uint32_t a_off[MBS];
-#pragma unroll
-    for (int mb = 0; mb < MBS; ++mb)
-        a_off[mb] = (static_cast<uint32_t>(row_begin + min(mb * 32 + r0, rows - 1)) * K + 8 * (threadIdx.x & 7)) * 2u;
+    // this thread's activation sources (byte offsets from A): row mb*32 + t/8 of every block, piece t%8.
+    // All blocks but the last hold 32 rows, so their rows lie a fixed stride apart; rows past the end
+    // of the last block re-read the tile's last row.
+    const int r0 = tid >> 3;
+    const uint32_t piece = 16u * (tid & 7);
+    const uint32_t a_first = static_cast<uint32_t>(row_begin + r0) * K * 2u + piece;
+    const uint32_t a_last = static_cast<uint32_t>(row_begin + min((MBS - 1) * 32 + r0, rows - 1)) * K * 2u + piece;
+    const uint32_t a_stride = 64u * K;          // 32 rows, in bytes
 
     f32x16 acc[MBS][NF];
+    // cleared in place, in the accumulation registers: a zero constant would be parked in 16 registers for all
+    // tile heights and copied from there
 #pragma unroll
     for (int mb = 0; mb < MBS; ++mb)
 #pragma unroll
         for (int j = 0; j < NF; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mb][j][v] = 0.f;
+            for (int v = 0; v < 16; ++v) asm volatile("v_accvgpr_write_b32 %0, 0" : "=a"(acc[mb][j][v]));
 
-    ARegs<MBS> areg;
-    BFrags<NF> ring[kRing];
-    auto fetch_a = [&](int chunk) {
-        const uint32_t step_off = static_cast<uint32_t>(chunk) * (kKC * 2);
+    // Pipeline depth.  Issue order inside a step is activations, then weights, so the loads younger
+    // than the ones awaited are known at compile time.
+    //   up to 6 row blocks: activations 2 steps ahead, ring of 4 weight steps.  Step c issues A(c+2),
+    //     B(c+3); half-way through it waits for A(c+1) (younger: B(c+2), A(c+2), B(c+3)), which also
+    //     covers the older B(c+1), and stages A(c+1).
+    //   7 or 8 row blocks (no registers for more): activations 1 step ahead, ring of 3.  Step c issues
+    //     A(c+1), B(c+2); just before its barrier it waits for A(c+1) (younger: B(c+2)) and stages it.
+    constexpr int AD = MBS <= 6 ? 2 : 1;
+    constexpr int R = AD + 2;                   // weight ring; register indices repeat with period R
+    constexpr int kB = kKS * NF;                // loads of one weight step
+    constexpr int kStageAfter = AD == 2 ? Units<MBS>::U / 2 - 1 : Units<MBS>::U - 2;
+    constexpr int kYounger = AD == 2 ? 2 * kB + MBS : kB;
+    ARegs<MBS> areg[AD];
+    BFrags<NF> ring[R];
+    uint4 af[2][Units<MBS>::G];
+    // the per-block and per-step parts of the address are uniform: they go into the scalar base, and the
+    // per-thread part is the same register for every block but the last
+    auto fetch_a = [&](ARegs<MBS>& dst, int chunk) {
+        const char* base = reinterpret_cast<const char*>(A) + static_cast<size_t>(chunk) * (kKC * 2);
 #pragma unroll
-        for (int mb = 0; mb < MBS; ++mb) ld_pinned<0>(areg.v[mb], a_off[mb] + step_off, A);
+        for (int mb = 0; mb + 1 < MBS; ++mb) ld_pinned<0>(dst.v[mb], a_first, base + static_cast<size_t>(mb) * a_stride);
+        ld_pinned<0>(dst.v[MBS - 1], a_last, base);
     };
     auto fetch_b = [&](BFrags<NF>& dst, int chunk) {
         load_b(dst, static_cast<uint32_t>(chunk) * (kKS * 2048) + lane * 16, wave_base);
     };
-    // Blocks that run at the same time start their sweep over the reduction dimension at different
-    // steps (and wrap around), so that concurrent waves do not walk their weight streams, which lie a
-    // power of two apart, in lockstep.  The phase depends only on (expert, row tile, column group),
-    // never on the launch shape, so a launch over all experts and a launch over one expert sum in the
-    // same order (bitwise equal results).
+    // Blocks that share a weight stream or an activation tile start their sweep over the reduction
+    // dimension at the same step (and wrap around), other blocks at other steps, so that concurrent
+    // waves do not all walk their weight streams, which lie a power of two apart, in lockstep.  The
+    // phase never depends on the launch shape, so a launch over all experts and a launch over one
+    // expert sum in the same order (bitwise equal results).
     const int phase = static_cast<int>(phase_key % static_cast<unsigned>(chunks));
     auto at = [&](int i) { const int c = phase + i; return c >= chunks ? c - chunks : c; };   // i < chunks
-    fetch_a(at(0));
-    fetch_b(ring[0], at(0));
-    fetch_b(ring[1], at(min(1, last)));
-    wait_step(areg, ring[0]);                  // everything but the newest weight step has landed
-    store_a(areg, lds[0]);
-    __syncthreads();
-
-#define FFN_STEP(I)                                                                   \
-    {                                                                                 \
-        const int ci = c + (I);                                                       \
-        fetch_a(at(min(ci + 1, last)));                                               \
-        fetch_b(ring[((I) + 2) % kRing], at(min(ci + 2, last)));                      \
-        mma_step(acc, lds[(ci) & 1], ring[(I)], lane);                                \
-        wait_step(areg, ring[((I) + 1) % kRing]);                                     \
-        store_a(areg, lds[(ci + 1) & 1]);                                             \
-        __syncthreads();                                                              \
-    }
     int c = 0;
-    for (; c + kRing <= chunks; c += kRing) {
-        FFN_STEP(0) FFN_STEP(1) FFN_STEP(2)
+    if (chunks >= R) {
+        asm volatile("; pipeline begin");       // from here to the matching end the build allows no spill code
+        // Prologue.  AD = 2: A(0) B(0) B(1) A(1) B(2);  AD = 1: A(0) B(0) B(1).  Then wait for A(0), B(0).
+        fetch_a(areg[0], at(0));
+        fetch_b(ring[0], at(0));
+        fetch_b(ring[1], at(1));
+        if (AD == 2) {
+            fetch_a(areg[1], at(1));
+            fetch_b(ring[2], at(2));
+        }
+        wait_loads<(AD == 2 ? 2 * kB + MBS : kB)>(areg[0], ring[0]);
+        store_a(areg[0], lds[0], tid);
+        __syncthreads();
+        read_unit<MBS, 0>(af[0], lds[0], lane);
+        // Step c = c0 + I, c0 a multiple of R (even when AD = 2): all register indices are static.
+#define FFN_STEP(I)                                                                                        \
+    {                                                                                                      \
+        const int ci = c + (I);                                                                            \
+        fetch_a(areg[((I) + AD) % AD], at(min(ci + AD, last)));                                            \
+        fetch_b(ring[((I) + AD + 1) % R], at(min(ci + AD + 1, last)));                                     \
+        run_step<kStageAfter, kYounger>(acc, af, lds[ci & 1], lds[(ci + 1) & 1], ring[(I) % R],            \
+                                        areg[((I) + 1) % AD], ring[((I) + 1) % R], lane, tid);                  \
     }
-    const int left = chunks - c;               // 0..2 steps that do not fill a group
-    if (left > 0) FFN_STEP(0)
-    if (left > 1) FFN_STEP(1)
+        for (; c + R <= chunks; c += R) {
+            FFN_STEP(0) FFN_STEP(1) FFN_STEP(2)
+            if (R == 4) FFN_STEP(3)
+        }
 #undef FFN_STEP
+        asm volatile("; pipeline end");
+    }
+    // the steps that do not fill a group of R, one by one and without overlap
+    for (; c < chunks; ++c) {
+        asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
+        fetch_a(areg[0], at(c));
+        fetch_b(ring[0], at(c));
+        slow_step(acc, af, lds[0], areg[0], ring[0], lane, tid);
+    }
     // Drain the prefetches nobody consumes, and only then let go of their destination registers: a
     // destination the compiler considers dead would be handed to something else (an LDS read, say)
     // while the load into it is still in flight.
     asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
 #pragma unroll
-    for (int r = 0; r < kRing; ++r)
+    for (int r = 0; r < R; ++r)
 #pragma unroll
         for (int ks = 0; ks < kKS; ++ks)
 #pragma unroll
             for (int j = 0; j < NF; ++j) asm volatile("" : : "v"(ring[r].v[ks][j]));
 #pragma unroll
-    for (int mb = 0; mb < MBS; ++mb) asm volatile("" : : "v"(areg.v[mb]));
+    for (int i = 0; i < AD; ++i)
+#pragma unroll
+        for (int mb = 0; mb < MBS; ++mb) asm volatile("" : : "v"(areg[i].v[mb]));
+    __syncthreads();                            // the last LDS reads are done before the epilogue reuses the LDS
+    tid = thread_id(wave_s);                    // rebuilt: the first copy need not survive the main loop
     // Epilogue through LDS (the activation buffers are free now): every wave applies the activation to
     // its accumulators and writes bf16 values into a row-major tile of the block's columns; then the
     // whole block stores that tile with 16 bytes per lane, whole 64-byte segments per row.  All rows
@@ -331,8 +437,8 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
     constexpr int kRowsPerIter = 256 / kLanesPerRow;
     char* tile = reinterpret_cast<char*>(&lds[0][0]);
     static_assert(kRowsPerPass * kTileRowBytes <= static_cast<int>(sizeof(lds)), "epilogue tile must fit the LDS buffers");
-    const int wave = threadIdx.x >> 6;
-    const int col_in = lane & 31, row_in = 4 * (lane >> 5);
+    const int wave = wave_s;
+    const int col_in = (tid & 31), row_in = 4 * ((tid & 63) >> 5);
 #pragma unroll
     for (int p0 = 0; p0 < MBS * 32; p0 += kRowsPerPass) {
         if (p0 > 0) __syncthreads();                    // the previous pass has been stored
@@ -353,12 +459,12 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
             }
         }
         __syncthreads();
-        const int seg = (threadIdx.x % kLanesPerRow) * 8;       // first of this lane's 8 columns inside the block
+        const int seg = (tid % kLanesPerRow) * 8;       // first of this lane's 8 columns inside the block
         const int src_wave = seg / W;
         const int out_unit = unit - wave + src_wave;            // unit of the wave that produced them
         if (out_unit < N / W) {
             uint16_t* cbase = C + static_cast<size_t>(out_unit) * W + (seg % W);
-            for (int r = threadIdx.x / kLanesPerRow; r < kRowsPerPass && p0 + r < rows; r += kRowsPerIter) {
+            for (int r = tid / kLanesPerRow; r < kRowsPerPass && p0 + r < rows; r += kRowsPerIter) {
                 const uint4 val = *reinterpret_cast<const uint4*>(tile + r * kTileRowBytes + seg * 2);
                 *reinterpret_cast<uint4*>(cbase + static_cast<size_t>(row_begin + p0 + r) * N) = val;
             }
@@ -366,67 +472,139 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
     }
 }
 
+// Work list of one launch: which (expert, rows) every row tile covers, in the order the tiles are
+// handed out.  Experts with more rows come first, so that the tiles that finish last are the short
+// ones; an expert's rows are split evenly over its tiles (in multiples of 32 rows), not into full
+// tiles and a small remainder.  Also clears the work counters of the two kernels that follow.
+//   plan[0..7], plan[8..15] : next work item of each of the 8 queues, up and down kernel
+//   plan[16]                : number of tiles
+//   plan[32 + 4 s ..]       : tile s = (expert, first row, rows, 0)
+constexpr int kPlanHeader = 32;
+
+__global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict__ offsets, int e_first, int e_count,
+                                                       int tile_m, int32_t* __restrict__ plan) {
+    __shared__ int n[256], first[256], order[256], tl[256];
+    const int t = threadIdx.x;
+    int cnt = 0, lo = 0;
+    if (t < e_count) {
+        lo = offsets[e_first + t];
+        cnt = offsets[e_first + t + 1] - lo;
+    }
+    n[t] = cnt;
+    first[t] = lo;
+    __syncthreads();
+    int rank = 0;                       // more rows first, equal counts by expert index: a permutation of 0..255
+    for (int u = 0; u < 256; ++u) rank += (n[u] > cnt || (n[u] == cnt && u < t)) ? 1 : 0;
+    order[rank] = t;
+    __syncthreads();
+    const int mine = order[t], my_n = n[mine];
+    const int my_tiles = (my_n + tile_m - 1) / tile_m;
+    tl[t] = my_tiles;
+    __syncthreads();
+    int start = 0;
+    for (int r = 0; r < t; ++r) start += tl[r];
+    if (my_tiles > 0) {
+        const int per_tile = min(tile_m, ((my_n + my_tiles - 1) / my_tiles + 31) & ~31);
+        int4* tiles = reinterpret_cast<int4*>(plan + kPlanHeader);
+        for (int mt = 0; mt < my_tiles; ++mt)
+            tiles[start + mt] = make_int4(e_first + mine, first[mine] + mt * per_tile, min(per_tile, my_n - mt * per_tile), 0);
+    }
+    if (t == 255) plan[16] = start + my_tiles;
+    if (t < 16) plan[t] = 0;
+}
+
 // C[rows of one expert tile, N] = A[rows, K] * B_e, B_e in packed fragment order.
-// A block is up to 256 rows of one expert (only the 32-row blocks that hold rows are computed) by
-// 4 waves; wave w owns column unit 4*(column group) + w for all rows.
+// A work item is one row tile (up to 256 rows of one expert; only the 32-row blocks that hold rows are
+// computed) by one column group of 4 units, one unit per wave, for all rows.
 // GATED (NF = 2): a unit is 32 output columns whose two fragments per k-step are (W_gate, W_in); the
 //   epilogue writes act(gate) * in.
 // otherwise a unit is 32 * NF output columns of W_out.
-// Weight fragments stream HBM -> registers through a ring of kRing buffers so that several KiB per
+// Weight fragments stream HBM -> registers through a ring of buffers so that several KiB per
 // wave are always in flight; the activation tile goes through LDS, double buffered.
+//
+// One block per compute unit stays resident and takes work items from 8 queues, one per XCD (blocks go
+// round-robin to the XCDs, each with its own L2, so blockIdx % 8 names the XCD): position q of a
+// queue decodes into 32-item runs of 2^mt_shift neighbouring row tiles x 32 / 2^mt_shift neighbouring
+// column groups.  Tiles of one expert then share its weight stream, and the column groups of a tile
+// share its activation tile, in that XCD's L2; groups of tiles are dealt to the queues in turn.  A
+// block whose own queue is empty helps with the others.
 template <bool GATED, int NF>
-__global__ __launch_bounds__(256) void ffn_mfma_kernel(const uint16_t* __restrict__ A, const int32_t* __restrict__ offsets,
-                                                       int e_first, int e_count, const char* __restrict__ W,
+__global__ __launch_bounds__(256) void ffn_mfma_kernel(const uint16_t* __restrict__ A, int32_t* __restrict__ plan,
+                                                       int counter_base, int e_first, const char* __restrict__ W,
                                                        size_t expert_stride_bytes, size_t block_offset_bytes,
                                                        uint16_t* __restrict__ C, int K, int N, int act, int y_chunks,
                                                        int mt_shift) {
     __shared__ uint4 lds[2][kTileM * kLdsRow];     // 2 x 36 KiB activation tiles, padded rows
-    // Block id -> (row-tile slot, column group).  Workgroups go round-robin to the 8 XCDs, each with its
-    // own L2, so the id is split into x = id % 8 (the XCD) and the position q in that XCD's queue; 32
-    // consecutive positions (about what an XCD runs at a time) are 2^mt_shift neighbouring row tiles x
-    // 32 / 2^mt_shift neighbouring column groups.  Tiles of one expert then share its weight stream, and
-    // the column groups of a tile share its activation tile, in that XCD's L2; the groups of tiles are
-    // dealt to the XCDs in turn so that the load is even (fewer tiles per group when there are few).
-    const unsigned xcd = blockIdx.x & 7u, q = blockIdx.x >> 3;
-    const unsigned ny = 32u >> mt_shift;           // column groups per run of 32; 1 << mt_shift row tiles
-    const unsigned yg = q & (ny - 1u), mt = (q / ny) & ((1u << mt_shift) - 1u), rest = q >> 5;
-    const unsigned y_chunk = rest % static_cast<unsigned>(y_chunks), tile_group = rest / static_cast<unsigned>(y_chunks);
-    const int slot = static_cast<int>((((tile_group << 3) + xcd) << mt_shift) + mt);
-    const int block_y = static_cast<int>(y_chunk * ny + yg);
-    int e, row_begin, rows;
-    if (!find_tile(offsets, e_first, e_count, kTileM, slot, e, row_begin, rows)) return;
+    __shared__ int sh_q, sh_x;
+    const int tiles = plan[16];
+    const unsigned per_group = 8u << mt_shift;
+    const unsigned total_q = (static_cast<unsigned>(tiles) + per_group - 1u) / per_group * static_cast<unsigned>(y_chunks) * 32u;
+    const int4* tile_list = reinterpret_cast<const int4*>(plan + kPlanHeader);
+    unsigned* counters = reinterpret_cast<unsigned*>(plan) + counter_base;
+    const unsigned home = blockIdx.x & 7u;
+    const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
+    for (bool first = true;; first = false) {
+        if (!first) __syncthreads();               // the previous item is done with the LDS and with sh_q
+        if (thread_id(wave) == 0) {
+            int got = -1;
+            unsigned x = home;
+            for (unsigned i = 0; i < 8u; ++i) {
+                x = (home + i) & 7u;
+                const unsigned v = atomicAdd(&counters[x], 1u);
+                if (v < total_q) { got = static_cast<int>(v); break; }
+            }
+            sh_q = got;
+            sh_x = static_cast<int>(x);
+        }
+        __syncthreads();
+        if (sh_q < 0) return;                      // every queue is empty (uniform for the block)
+        // The tile code below is compiled for eight tile heights; values that do not change from item to
+        // item would be hoisted out of this loop and held in registers across all of them.  The inputs
+        // are made opaque per iteration instead.
+        int Kl = K, Nl = N;
+        asm volatile("" : "+s"(Kl), "+s"(Nl));
+        const unsigned xcd = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(sh_x));
+        const unsigned q = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(sh_q));
+        const unsigned ny = 32u >> mt_shift;       // column groups per run of 32; 1 << mt_shift row tiles
+        const unsigned yg = q & (ny - 1u), mt = (q / ny) & ((1u << mt_shift) - 1u), rest = q >> 5;
+        const unsigned y_chunk = rest % static_cast<unsigned>(y_chunks), tile_group = rest / static_cast<unsigned>(y_chunks);
+        const int slot = static_cast<int>((((tile_group << 3) + xcd) << mt_shift) + mt);
+        const int block_y = static_cast<int>(y_chunk * ny + yg);
+        const int units = Nl / (32 * (GATED ? 1 : NF));
+        if (slot >= tiles || block_y * 4 >= units) continue;   // past the last tile or column group (uniform)
+        const int4 tile = tile_list[slot];         // the same for all lanes: kept in scalar registers
+        const int e = __builtin_amdgcn_readfirstlane(tile.x), row_begin = __builtin_amdgcn_readfirstlane(tile.y),
+                  rows = __builtin_amdgcn_readfirstlane(tile.z);
 
-    const int wave = threadIdx.x >> 6;
-    const int units = N / (32 * (GATED ? 1 : NF));
-    const int unit = block_y * 4 + wave;
-    const bool active = unit < units;              // a wave past the last unit recomputes the last one, stores nothing
-    const int u = active ? unit : units - 1;
-    const int steps16 = K / 16;
-    // fragment pair index and which half of the pair this wave reads
-    const int pair = (GATED || NF == 2) ? u : (u >> 1);
-    const int half = (GATED || NF == 2) ? 0 : (u & 1);
-    // start of this wave's fragment stream; the same for all lanes, so it is handed over in scalar registers
-    const char* wb = W + static_cast<size_t>(e - e_first) * expert_stride_bytes + block_offset_bytes +
-                     (static_cast<size_t>(pair) * steps16 * 128 + half * 64) * 16;
-    const uintptr_t wbi = reinterpret_cast<uintptr_t>(wb);
-    const uint32_t wb_lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(wbi))));
-    const uint32_t wb_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(wbi >> 32))));
-    const void* wave_w = reinterpret_cast<const void*>((static_cast<uintptr_t>(wb_hi) << 32) | static_cast<uintptr_t>(wb_lo));
-    if (block_y * 4 >= units) return;              // past the last column group (uniform for the block)
-    // The sweep over the reduction dimension starts at a step that depends on the expert and on the
-    // chunk of 8 column groups only: blocks that share a weight stream or an activation tile walk it
-    // together, other blocks are out of step with them.
-    const unsigned col_chunk = static_cast<unsigned>(block_y) >> ((GATED || NF == 2) ? 3 : 4);   // same for both unit widths
-    const unsigned key = static_cast<unsigned>(e) * 37u + col_chunk * 17u;
-    switch ((rows + 31) >> 5) {
-        case 1: ffn_tile<GATED, NF, 1>(lds, A, row_begin, rows, wave_w, C, K, N, unit, active, act, key); break;
-        case 2: ffn_tile<GATED, NF, 2>(lds, A, row_begin, rows, wave_w, C, K, N, unit, active, act, key); break;
-        case 3: ffn_tile<GATED, NF, 3>(lds, A, row_begin, rows, wave_w, C, K, N, unit, active, act, key); break;
-        case 4: ffn_tile<GATED, NF, 4>(lds, A, row_begin, rows, wave_w, C, K, N, unit, active, act, key); break;
-        case 5: ffn_tile<GATED, NF, 5>(lds, A, row_begin, rows, wave_w, C, K, N, unit, active, act, key); break;
-        case 6: ffn_tile<GATED, NF, 6>(lds, A, row_begin, rows, wave_w, C, K, N, unit, active, act, key); break;
-        case 7: ffn_tile<GATED, NF, 7>(lds, A, row_begin, rows, wave_w, C, K, N, unit, active, act, key); break;
-        default: ffn_tile<GATED, NF, 8>(lds, A, row_begin, rows, wave_w, C, K, N, unit, active, act, key); break;
+        const int unit = block_y * 4 + wave;
+        const bool active = unit < units;          // a wave past the last unit recomputes the last one, stores nothing
+        const int u = active ? unit : units - 1;
+        const int steps16 = Kl / 16;
+        // fragment pair index and which half of the pair this wave reads
+        const int pair = (GATED || NF == 2) ? u : (u >> 1);
+        const int half = (GATED || NF == 2) ? 0 : (u & 1);
+        // start of this wave's fragment stream; the same for all lanes, so it is handed over in scalar registers
+        const char* wb = W + static_cast<size_t>(e - e_first) * expert_stride_bytes + block_offset_bytes +
+                         (static_cast<size_t>(pair) * steps16 * 128 + half * 64) * 16;
+        const uintptr_t wbi = reinterpret_cast<uintptr_t>(wb);
+        const uint32_t wb_lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(wbi))));
+        const uint32_t wb_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(wbi >> 32))));
+        const void* wave_w = reinterpret_cast<const void*>((static_cast<uintptr_t>(wb_hi) << 32) | static_cast<uintptr_t>(wb_lo));
+        // The sweep over the reduction dimension starts at a step that depends on the expert and on the
+        // chunk of 8 column groups only: blocks that share a weight stream or an activation tile walk it
+        // together, other blocks are out of step with them.
+        const unsigned col_chunk = static_cast<unsigned>(block_y) >> ((GATED || NF == 2) ? 3 : 4);   // same for both unit widths
+        const unsigned key = static_cast<unsigned>(e) * 37u + col_chunk * 17u;
+        switch ((rows + 31) >> 5) {
+            case 1: ffn_tile<GATED, NF, 1>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave); break;
+            case 2: ffn_tile<GATED, NF, 2>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave); break;
+            case 3: ffn_tile<GATED, NF, 3>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave); break;
+            case 4: ffn_tile<GATED, NF, 4>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave); break;
+            case 5: ffn_tile<GATED, NF, 5>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave); break;
+            case 6: ffn_tile<GATED, NF, 6>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave); break;
+            case 7: ffn_tile<GATED, NF, 7>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave); break;
+            default: ffn_tile<GATED, NF, 8>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave); break;
+        }
     }
 }
 
@@ -501,6 +679,9 @@ __global__ __launch_bounds__(256) void copy_vec_kernel(const uint4* __restrict__
 
 }  // namespace
 
+size_t ffn_plan_tiles(const moe_cfg& c) { return static_cast<size_t>(c.T) * c.k / kTileM + c.E; }
+size_t ffn_plan_bytes(const moe_cfg& c) { return (kPlanHeader + 4 * ffn_plan_tiles(c)) * sizeof(int32_t); }
+
 int launch_pack(const moe_cfg& c, const void* Win, const void* Wgate, const void* Wout, void* packed, hipStream_t s) {
     const size_t df = static_cast<size_t>(c.d) * c.f;
     if (c.dtype == MOE_BF16) {
@@ -524,48 +705,54 @@ int launch_pack(const moe_cfg& c, const void* Win, const void* Wgate, const void
 }
 
 int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, int e_first, int e_count,
-                      const void* W, size_t expert_stride_bytes, long max_rows, void* H, void* Yp, hipStream_t s,
-                      hipEvent_t between) {
+                      const void* W, size_t expert_stride_bytes, long max_rows, void* H, void* Yp, int32_t* plan,
+                      hipStream_t s, hipEvent_t between) {
     if (max_rows <= 0 || e_count <= 0) return MOE_OK;
     const size_t df = static_cast<size_t>(c.d) * c.f;
     if (c.dtype == MOE_BF16) {
-        // grid.x = row-tile slots (fastest varying, padded to the 8 XCDs so that the blocks sharing one
-        // activation tile land on one XCD and its L2), grid.y = groups of 4 column units
-        // one-dimensional grid: 8 XCDs x (groups of 4 row-tile slots per XCD) x (chunks of 8 column groups) x 32
-        long slots = max_rows / kTileM + e_count;
+        // Work items: 8 queues x (groups of row tiles per queue) x (chunks of column groups) x 32; the
+        // resident blocks take them until the queues are empty.
+        const long slots = max_rows / kTileM + e_count;                // upper bound of the number of row tiles
+        if (slots > static_cast<long>(ffn_plan_tiles(c)))
+            return fail(MOE_ERR_INVALID_ARG, "more row tiles (%ld) than the workspace plans for", slots);
         const int mt_shift = slots >= 32 ? 2 : slots >= 16 ? 1 : 0;   // row tiles per group: 4, 2 or 1
-        const long tile_groups = (slots + (8L << mt_shift) - 1) / (8L << mt_shift);   // per XCD
-        auto grid_for = [&](int col_groups, int& y_chunks) {
+        const long tile_groups = (slots + (8L << mt_shift) - 1) / (8L << mt_shift);   // per queue
+        auto items_for = [&](int col_groups, int& y_chunks) {
             const int ny = 32 >> mt_shift;
             y_chunks = (col_groups + ny - 1) / ny;
             return tile_groups * y_chunks * 32 * 8;
         };
+        static const int n_cu = [] {
+            int dev = 0, n = 0;
+            if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+            return n;
+        }();
+        auto grid_for = [&](long items) { return dim3(static_cast<unsigned>(items < n_cu ? items : n_cu)); };
+        hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, s, offsets, e_first, e_count, kTileM, plan);
+        MOE_LAUNCH_CHECK("ffn_plan_kernel");
         const size_t down_off = 2 * df * 2;
         dim3 block(256);
         int yc = 0;
-        long blocks = grid_for((c.f / 32 + 3) / 4, yc);
-        if (blocks > 0x7fffffffL) return fail(MOE_ERR_UNSUPPORTED, "too many blocks for one launch (%ld)", blocks);
-        hipLaunchKernelGGL((ffn_mfma_kernel<true, 2>), dim3(static_cast<unsigned>(blocks)), block, 0, s,
-                           static_cast<const uint16_t*>(Xp), offsets, e_first, e_count, static_cast<const char*>(W),
-                           expert_stride_bytes, size_t(0), static_cast<uint16_t*>(H), c.d, c.f, c.act, yc, mt_shift);
+        long items = items_for((c.f / 32 + 3) / 4, yc);
+        if (items > 0x7fffffffL) return fail(MOE_ERR_UNSUPPORTED, "too many work items for one launch (%ld)", items);
+        hipLaunchKernelGGL((ffn_mfma_kernel<true, 2>), grid_for(items), block, 0, s, static_cast<const uint16_t*>(Xp), plan, 0,
+                           e_first, static_cast<const char*>(W), expert_stride_bytes, size_t(0), static_cast<uint16_t*>(H),
+                           c.d, c.f, c.act, yc, mt_shift);
         MOE_LAUNCH_CHECK("ffn_mfma_kernel<up>");
         if (between != nullptr) MOE_HIP_CHECK(hipEventRecord(between, s));
         // down-projection: narrow (32-column) units when wide ones would leave compute units idle
         const long tiles_hint = (max_rows + kTileM - 1) / kTileM > e_count ? (max_rows + kTileM - 1) / kTileM : e_count;
         const bool narrow = tiles_hint * ((c.d / 64 + 3) / 4) < 2 * 256;
-        if (narrow) {
-            blocks = grid_for((c.d / 32 + 3) / 4, yc);
-            if (blocks > 0x7fffffffL) return fail(MOE_ERR_UNSUPPORTED, "too many blocks for one launch (%ld)", blocks);
-            hipLaunchKernelGGL((ffn_mfma_kernel<false, 1>), dim3(static_cast<unsigned>(blocks)), block, 0, s,
-                               static_cast<const uint16_t*>(H), offsets, e_first, e_count, static_cast<const char*>(W),
-                               expert_stride_bytes, down_off, static_cast<uint16_t*>(Yp), c.f, c.d, c.act, yc, mt_shift);
-        } else {
-            blocks = grid_for((c.d / 64 + 3) / 4, yc);
-            if (blocks > 0x7fffffffL) return fail(MOE_ERR_UNSUPPORTED, "too many blocks for one launch (%ld)", blocks);
-            hipLaunchKernelGGL((ffn_mfma_kernel<false, 2>), dim3(static_cast<unsigned>(blocks)), block, 0, s,
-                               static_cast<const uint16_t*>(H), offsets, e_first, e_count, static_cast<const char*>(W),
-                               expert_stride_bytes, down_off, static_cast<uint16_t*>(Yp), c.f, c.d, c.act, yc, mt_shift);
-        }
+        items = items_for(((narrow ? c.d / 32 : c.d / 64) + 3) / 4, yc);
+        if (items > 0x7fffffffL) return fail(MOE_ERR_UNSUPPORTED, "too many work items for one launch (%ld)", items);
+        if (narrow)
+            hipLaunchKernelGGL((ffn_mfma_kernel<false, 1>), grid_for(items), block, 0, s, static_cast<const uint16_t*>(H), plan, 8,
+                               e_first, static_cast<const char*>(W), expert_stride_bytes, down_off, static_cast<uint16_t*>(Yp),
+                               c.f, c.d, c.act, yc, mt_shift);
+        else
+            hipLaunchKernelGGL((ffn_mfma_kernel<false, 2>), grid_for(items), block, 0, s, static_cast<const uint16_t*>(H), plan, 8,
+                               e_first, static_cast<const char*>(W), expert_stride_bytes, down_off, static_cast<uint16_t*>(Yp),
+                               c.f, c.d, c.act, yc, mt_shift);
         MOE_LAUNCH_CHECK("ffn_mfma_kernel<down>");
         return MOE_OK;
     }

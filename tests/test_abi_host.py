@@ -91,3 +91,41 @@ def test_null_pointers_are_rejected_before_launch():
     assert b"expert_bytes" in L.moe_last_error()
     assert L.moe_stream_ctx_create(C.byref(cfg), C.c_void_p(al), 3 * 64 * 64 * 2, C.c_void_p(al), 0, C.byref(h)) == -1
     assert b"K must be" in L.moe_last_error()
+
+
+def test_build_refuses_spill_code_inside_a_load_pipeline():
+    """The build's assembly check: scratch accesses are tolerated outside the bracketed regions and outside
+    nested loops of the named kernels, and refused inside them."""
+    from paper_2106_10715_amd.build import check_no_spill
+    ok = "\n".join([
+        "_ZN3moe8ffn_mfma_kernelEv: ; @x",
+        "\tscratch_store_dword off, v1, off",
+        "\t; pipeline begin",
+        "\tglobal_load_dwordx4 v[0:3], v4, s[0:1]",
+        "\t; pipeline end",
+        "\tscratch_load_dword v1, off, off",
+        ".LBB0_1:                                ; =>This Inner Loop Header: Depth=1",
+        "\tscratch_load_dword v1, off, off",
+        ".LBB0_2:                                ;   Parent Loop BB0_1 Depth=1",
+        "                                        ; =>  This Inner Loop Header: Depth=2",
+        "\ts_nop 0",
+        "; %bb.3:                                ;   in Loop: Header=BB0_1 Depth=1",
+        "\tscratch_load_dword v1, off, off",
+        "\t.end_amdhsa_kernel",
+        "_ZN3moe5otherEv: ; @y",
+        ".LBB1_1:                                ;   Parent Loop BB1_0 Depth=1",
+        "                                        ; =>  This Inner Loop Header: Depth=2",
+        "\tscratch_load_dword v1, off, off",
+    ])
+    check_no_spill(ok, "ffn_mfma")
+    bracketed = ok.replace("\tglobal_load_dwordx4 v[0:3], v4, s[0:1]", "\tscratch_store_dword off, v9, off")
+    with pytest.raises(RuntimeError, match="spill code"):
+        check_no_spill(bracketed, "ffn_mfma")
+    nested = "\n".join([
+        "_ZN3moe8ffn_mfma_kernelEv: ; @x",
+        ".LBB0_5:                                ;   Parent Loop BB0_1 Depth=1",
+        "                                        ; =>  This Inner Loop Header: Depth=2",
+        "\tscratch_load_dword v1, off, off",
+    ])
+    with pytest.raises(RuntimeError, match="spill code"):
+        check_no_spill(nested, "ffn_mfma")
