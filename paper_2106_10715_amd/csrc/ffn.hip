@@ -14,6 +14,8 @@
 // fp32 path: plain LDS-tiled FMA kernel (small-shape correctness vehicle).
 #include "common.h"
 
+#include <type_traits>
+
 namespace moe {
 namespace {
 
@@ -442,22 +444,29 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
 #pragma unroll
     for (int p0 = 0; p0 < MBS * 32; p0 += kRowsPerPass) {
         if (p0 > 0) __syncthreads();                    // the previous pass has been stored
+        // the choice of activation is taken once per pass, outside the value loops, so that the sixteen
+        // independent evaluations of a fragment can overlap
+        auto fill = [&](auto exact) {
 #pragma unroll
-        for (int mb = p0 / 32; mb < MBS && mb < (p0 + kRowsPerPass) / 32; ++mb) {
+            for (int mb = p0 / 32; mb < MBS && mb < (p0 + kRowsPerPass) / 32; ++mb) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                // accumulator layout of the 32x32 MFMA: lane holds column lane%32, rows 8*(v/4) + 4*(lane/32) + v%4
-                const int r = mb * 32 + 8 * (v >> 2) + row_in + (v & 3) - p0;
-                uint16_t* trow = reinterpret_cast<uint16_t*>(tile + r * kTileRowBytes) + wave * W + col_in;
-                if (GATED) {
-                    const float h = act_fn_bf16(acc[mb][0][v], act) * acc[mb][1][v];
-                    trow[0] = __builtin_bit_cast(uint16_t, static_cast<__bf16>(h));
-                } else {
+                for (int v = 0; v < 16; ++v) {
+                    // accumulator layout of the 32x32 MFMA: lane holds column lane%32, rows 8*(v/4) + 4*(lane/32) + v%4
+                    const int r = mb * 32 + 8 * (v >> 2) + row_in + (v & 3) - p0;
+                    uint16_t* trow = reinterpret_cast<uint16_t*>(tile + r * kTileRowBytes) + wave * W + col_in;
+                    if constexpr (GATED) {
+                        const float h = act_fn_bf16(acc[mb][0][v], decltype(exact)::value ? 0 : 1) * acc[mb][NF - 1][v];
+                        trow[0] = __builtin_bit_cast(uint16_t, static_cast<__bf16>(h));
+                    } else {
 #pragma unroll
-                    for (int j = 0; j < NF; ++j) trow[32 * j] = __builtin_bit_cast(uint16_t, static_cast<__bf16>(acc[mb][j][v]));
+                        for (int j = 0; j < NF; ++j)
+                            trow[32 * j] = __builtin_bit_cast(uint16_t, static_cast<__bf16>(acc[mb][j][v]));
+                    }
                 }
             }
-        }
+        };
+        if (!GATED || act == 0) fill(std::true_type{});
+        else fill(std::false_type{});
         __syncthreads();
         const int seg = (tid % kLanesPerRow) * 8;       // first of this lane's 8 columns inside the block
         const int src_wave = seg / W;
