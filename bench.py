@@ -32,6 +32,13 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4a", "c4b", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--streamed", action="store_true", help="run the workload with host-streamed experts even if it is defined resident")
+    ap.add_argument("--slots", type=int, default=2, help="device slots of the streamed mode")
+    ap.add_argument("--order", default="ascending", choices=["ascending", "greedy"],
+                    help="streamed mode: expert execution order (greedy = the paper's Section 6.2 schedule)")
+    ap.add_argument("--tokens-per-load", type=float, default=None,
+                    help="greedy order: tokens whose computation lasts as long as one expert load "
+                         "(default: from the published peaks, beta = expert bytes / 64 GB/s, alpha = 6 d f / 2.5 PFLOP/s)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic, for scaling "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -123,14 +130,21 @@ def main():
     torch.cuda.set_device(0)
     M.lib()                                     # fails loudly if the HIP library is not built
     wl = W.CONFIGS[args.workload]
+    if args.streamed and not wl.streamed:
+        import dataclasses
+        wl = dataclasses.replace(wl, streamed=True, name=wl.name + "-streamed")
     t_setup = time.perf_counter()
     L = H.build_layer(wl, resident=not wl.streamed, host_copy=wl.streamed)
     print(f"[bench] {wl.name}: inputs resident after {time.perf_counter() - t_setup:.1f} s", file=sys.stderr, flush=True)
     eb = M.moe_expert_bytes(L.cfg)
     ctx = None
     if wl.streamed:
-        slots = torch.empty((2, eb), dtype=torch.uint8, device="cuda")
-        ctx = M.StreamCtx(L.cfg, L.host_packed, slots, 2)
+        slots = torch.empty((args.slots, eb), dtype=torch.uint8, device="cuda")
+        ctx = M.StreamCtx(L.cfg, L.host_packed, slots, args.slots)
+        if args.order == "greedy":
+            # Section 6.2 takes alpha and beta from the peak rates of the machine
+            tpl = args.tokens_per_load or (eb / 64e9) / (6.0 * wl.d * wl.f / (MFMA_BF16_PEAK_TFLOPS * 1e12))
+            ctx.set_order(M.ORDER_GREEDY, tpl, args.slots)
 
     def step():
         M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, ctx, L.y, L.ws)
@@ -181,7 +195,8 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "T": wl.T, "d_model": d, "d_ff": f, "experts": wl.E, "top_k": wl.k,
-                   "mode": "host-streamed experts (K=2 slots)" if wl.streamed else "experts resident in HBM",
+                   "mode": f"host-streamed experts (K={args.slots} slots, {args.order} order)" if wl.streamed
+                           else "experts resident in HBM",
                    "non_empty_experts": live, "max_tokens_per_expert": int(counts.max()),
                    "min_tokens_per_expert": int(counts.min())},
     }
@@ -226,6 +241,9 @@ def main():
                            "note": "peak = PCIe Gen5 x16 raw, one direction"}
         out["streaming"] = {"h2d_gbs": h2d, "copy_window_ms": cm, "step_ms": ms_per_step,
                             "copy_share_of_step": cm / ms_per_step, "experts_loaded_per_step": live}
+        if args.order == "greedy":
+            order, ok = ctx.last_order()
+            out["streaming"].update({"order_first": order[:8], "order_last": order[-4:], "constraints_satisfiable": ok})
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, counts, offsets.cpu().numpy(), perm.cpu().numpy())
     if ctx is not None:

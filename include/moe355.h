@@ -151,6 +151,44 @@ int moe_stream_ctx_create(const moe_cfg* cfg, const void* host_experts, size_t e
 int moe_stream_ctx_destroy(moe_stream_ctx* sctx);
 
 /*
+ * Execution order of offloaded experts (Section 6.2, "Scheduling Strategy for Offloading").
+ *
+ * With alpha_i the computation time of expert i (proportional to its token count), beta the loading
+ * time of one expert (the same for all) and K the number of experts loads may run ahead, the paper
+ * asks for an order o_1..o_T with, for every t,
+ *     sum_{i<t} alpha_{o_i} >= (t - 1) beta     and     sum_{i<t} alpha_{o_i} <= (t + K - 1) beta,
+ * found greedily; it does not print the rule.  moe_schedule_order takes, at every position, the
+ * remaining non-empty expert with the most tokens that keeps the second constraint, else the one
+ * with the fewest (ties: lower expert id).  Times are given in tokens: tokens_per_load =
+ * beta / (computation time of one token) > 0.
+ *
+ *   counts  host [E], tokens per expert (>= 0); experts with 0 tokens are left out of the order
+ *   order   host [E] out: expert ids in execution order; *n_order = how many (the non-empty ones)
+ *   satisfiable  host out, may be NULL: 1 if the order meets both constraints for all t, else 0
+ *                (an order is returned either way)
+ * Pure host function; E in [1, 256], K >= 0.  Errors: MOE_ERR_INVALID_ARG.
+ */
+#define MOE_ORDER_ASCENDING 0   /* experts in ascending id (the naive order of Figure 4a) */
+#define MOE_ORDER_GREEDY 1      /* moe_schedule_order on the counts of each call (Figure 4b) */
+int moe_schedule_order(const int32_t* counts, int32_t E, double tokens_per_load, int32_t K, int32_t* order,
+                       int32_t* n_order, int32_t* satisfiable);
+
+/*
+ * Which order streamed moe_layer_forward calls on this context load and run their experts in
+ * (default MOE_ORDER_ASCENDING).  tokens_per_load and K are those of moe_schedule_order and are
+ * ignored for MOE_ORDER_ASCENDING; K here is the K of the constraint, independent of the number of
+ * device slots the context owns (slots are always reused safely through events, in any order).
+ * The result of the layer does not depend on the order (bitwise).
+ */
+int moe_stream_ctx_set_order(moe_stream_ctx* sctx, int32_t policy, double tokens_per_load, int32_t K);
+
+/*
+ * The order the last streamed moe_layer_forward on this context used: order host [E] out,
+ * *n_order experts; *satisfiable (may be NULL) as in moe_schedule_order, 0 for MOE_ORDER_ASCENDING.
+ */
+int moe_stream_ctx_last_order(const moe_stream_ctx* sctx, int32_t* order, int32_t* n_order, int32_t* satisfiable);
+
+/*
  * Figures of the last streamed moe_layer_forward on this context; waits for that call's work to
  * finish.  n_loaded = experts copied; bytes = n_loaded * expert_bytes; copy_ms = first copy start to
  * last copy end on the copy stream.  Any pointer may be NULL.

@@ -58,6 +58,10 @@ def lib() -> C.CDLL:
             "moe_stream_ctx_create": [cfgp, p, C.c_size_t, p, C.c_int32, C.POINTER(C.c_void_p)],
             "moe_stream_ctx_destroy": [p],
             "moe_stream_ctx_stats": [p, C.POINTER(C.c_int32), C.POINTER(C.c_size_t), C.POINTER(C.c_float)],
+            "moe_schedule_order": [C.POINTER(C.c_int32), C.c_int32, C.c_double, C.c_int32, C.POINTER(C.c_int32),
+                                   C.POINTER(C.c_int32), C.POINTER(C.c_int32)],
+            "moe_stream_ctx_set_order": [p, C.c_int32, C.c_double, C.c_int32],
+            "moe_stream_ctx_last_order": [p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)],
             "moe_stage_timing_enable": [C.c_int32],
             "moe_stage_timing_read": [C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)],
             "moe_stage_timing_disable": [],
@@ -144,6 +148,15 @@ class StreamCtx:
         _check(lib().moe_stream_ctx_stats(self._h, C.byref(n), C.byref(b), C.byref(ms)))
         return {"n_loaded": n.value, "bytes": b.value, "copy_ms": ms.value}
 
+    def set_order(self, policy: int, tokens_per_load: float = 1.0, K: int = 0) -> None:
+        _check(lib().moe_stream_ctx_set_order(self._h, policy, tokens_per_load, K))
+
+    def last_order(self):
+        order = (C.c_int32 * 256)()
+        n, ok = C.c_int32(0), C.c_int32(0)
+        _check(lib().moe_stream_ctx_last_order(self._h, order, C.byref(n), C.byref(ok)))
+        return list(order[:n.value]), bool(ok.value)
+
     def close(self):
         if self._h:
             lib().moe_stream_ctx_destroy(self._h)
@@ -159,6 +172,19 @@ class StreamCtx:
 def moe_layer_forward(cfg, x, W_g, gate_bias, W_packed, sctx: Optional[StreamCtx], y, ws, stream=None) -> None:
     _check(lib().moe_layer_forward(C.byref(cfg), _ptr(x), _ptr(W_g), _ptr(gate_bias), _ptr(W_packed),
                                    sctx.handle if sctx is not None else None, _ptr(y), _ptr(ws), _stream(stream)))
+
+
+ORDER_ASCENDING, ORDER_GREEDY = 0, 1
+
+
+def moe_schedule_order(counts, tokens_per_load: float, K: int):
+    """(order of the non-empty experts, satisfiable) for host token counts; argument marshalling only."""
+    E = len(counts)
+    c = (C.c_int32 * E)(*[int(v) for v in counts])
+    order = (C.c_int32 * E)()
+    n, ok = C.c_int32(0), C.c_int32(0)
+    _check(lib().moe_schedule_order(c, E, float(tokens_per_load), int(K), order, C.byref(n), C.byref(ok)))
+    return list(order[:n.value]), bool(ok.value)
 
 
 STAGES = ("route", "permute", "ffn_up", "ffn_down", "combine")

@@ -80,6 +80,11 @@ struct moe_stream_ctx {
     bool timed;
     int32_t* h_counts;         // pinned [256]
     int n_loaded;
+    int policy;                // MOE_ORDER_ASCENDING or MOE_ORDER_GREEDY
+    double tokens_per_load;    // for the greedy order: tokens whose computation lasts as long as one load
+    int order_K;               // K of the order's second constraint
+    int satisfiable;           // whether the last greedy order met both constraints
+    int32_t order[256];
 };
 
 // Optional per-stage event timing of resident moe_layer_forward calls (measurement aid).
@@ -218,10 +223,20 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
         // The host has to know which experts hold tokens (and how many) before it can queue loads.
         MOE_HIP_CHECK(hipMemcpyAsync(sctx->h_counts, counts, sizeof(int32_t) * c.E, hipMemcpyDeviceToHost, s));
         MOE_HIP_CHECK(hipStreamSynchronize(s));
+        // execution order of the experts that hold tokens (experts without tokens are never loaded)
+        int n_order = 0;
+        if (sctx->policy == MOE_ORDER_GREEDY) {
+            if (int rc = schedule_order(sctx->h_counts, c.E, sctx->tokens_per_load, sctx->order_K, sctx->order, &n_order,
+                                        &sctx->satisfiable))
+                return rc;
+        } else {
+            for (int e = 0; e < c.E; ++e)
+                if (sctx->h_counts[e] > 0) sctx->order[n_order++] = e;
+        }
         int i = 0;
-        for (int e = 0; e < c.E; ++e) {
+        for (int pos = 0; pos < n_order; ++pos) {
+            const int e = sctx->order[pos];
             const int n_e = sctx->h_counts[e];
-            if (n_e <= 0) continue;                       // experts without tokens are never loaded
             const int slot = i % sctx->K;
             char* dst = sctx->dev_slots + static_cast<size_t>(slot) * eb;
             // the load may not overwrite a slot an earlier expert (of this or the previous call) still reads
@@ -325,6 +340,44 @@ int moe_stream_ctx_create(const moe_cfg* cfg, const void* host_experts, size_t e
         return rc;
     }
     *out = ctx;
+    return MOE_OK;
+}
+
+int moe_schedule_order(const int32_t* counts, int32_t E, double tokens_per_load, int32_t K, int32_t* order,
+                       int32_t* n_order, int32_t* satisfiable) {
+    REQUIRE(counts, "counts"); REQUIRE(order, "order"); REQUIRE(n_order, "n_order");
+    if (E < 1 || E > 256) return fail(MOE_ERR_INVALID_ARG, "E must be in [1, 256] (got %d)", E);
+    if (K < 0) return fail(MOE_ERR_INVALID_ARG, "K must not be negative (got %d)", K);
+    if (!(tokens_per_load > 0.0)) return fail(MOE_ERR_INVALID_ARG, "tokens_per_load must be positive");
+    for (int e = 0; e < E; ++e)
+        if (counts[e] < 0) return fail(MOE_ERR_INVALID_ARG, "counts[%d] is negative", e);
+    int n = 0, ok = 0;
+    if (int rc = schedule_order(counts, E, tokens_per_load, K, order, &n, &ok)) return rc;
+    *n_order = n;
+    if (satisfiable != nullptr) *satisfiable = ok;
+    return MOE_OK;
+}
+
+int moe_stream_ctx_set_order(moe_stream_ctx* ctx, int32_t policy, double tokens_per_load, int32_t K) {
+    REQUIRE(ctx, "ctx");
+    if (policy != MOE_ORDER_ASCENDING && policy != MOE_ORDER_GREEDY)
+        return fail(MOE_ERR_INVALID_ARG, "unknown order policy %d", policy);
+    if (policy == MOE_ORDER_GREEDY) {
+        if (!(tokens_per_load > 0.0)) return fail(MOE_ERR_INVALID_ARG, "tokens_per_load must be positive");
+        if (K < 0) return fail(MOE_ERR_INVALID_ARG, "K must not be negative (got %d)", K);
+    }
+    ctx->policy = policy;
+    ctx->tokens_per_load = tokens_per_load;
+    ctx->order_K = K;
+    ctx->satisfiable = 0;
+    return MOE_OK;
+}
+
+int moe_stream_ctx_last_order(const moe_stream_ctx* ctx, int32_t* order, int32_t* n_order, int32_t* satisfiable) {
+    REQUIRE(ctx, "ctx"); REQUIRE(order, "order"); REQUIRE(n_order, "n_order");
+    for (int i = 0; i < ctx->n_loaded; ++i) order[i] = ctx->order[i];
+    *n_order = ctx->n_loaded;
+    if (satisfiable != nullptr) *satisfiable = ctx->policy == MOE_ORDER_GREEDY ? ctx->satisfiable : 0;
     return MOE_OK;
 }
 

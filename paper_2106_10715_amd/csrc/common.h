@@ -74,6 +74,9 @@ int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, 
 // `plan`: ffn_plan_bytes(c) bytes of workspace, rewritten by every launch_expert_ffn (room for ffn_plan_tiles(c) row tiles).
 size_t ffn_plan_tiles(const moe_cfg& c);
 size_t ffn_plan_bytes(const moe_cfg& c);
+// Greedy execution order of the non-empty experts (host arrays); see schedule.hip.
+int schedule_order(const int32_t* counts, int E, double tokens_per_load, int K, int32_t* order, int* n_order,
+                   int* satisfiable);
 int launch_combine(const moe_cfg& c, const void* Yp, const int32_t* inv, const float* w, void* y, hipStream_t s);
 
 }  // namespace moe

@@ -128,3 +128,36 @@ def test_streamed_equals_resident_bitwise(wl, K):
     ctx.close()
     y_ref = oracle_layer(wl)[0]
     assert rel_l2(H.to_f64(y_res), y_ref) <= TOL[wl.dtype]
+
+
+@pytest.mark.parametrize("K,slots_n", [(0, 2), (2, 2), (2, 4), (6, 8)])
+def test_streamed_greedy_order_is_the_oracles_and_changes_nothing(K, slots_n):
+    """Section 6.2: the experts are loaded and run in the greedy order of the call's own token counts; the
+    order equals the oracle's for the oracle's counts, and the layer output stays bitwise the resident one."""
+    from oracle import schedule_oracle as S
+    wl = W.Workload("zipf-small", T=700, d=256, f=512, E=16, k=2, dtype="bf16", seed=77, zipf_s=1.2, n_dead=2)
+    L = H.build_layer(wl, host_copy=True)
+    M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)
+    torch.cuda.synchronize()
+    y_res = L.y.clone()
+    _, r, p, _ = oracle_layer(wl)
+    counts = [int(c) for c in p.counts]
+    eb = M.moe_expert_bytes(L.cfg)
+    slots = torch.empty((slots_n, eb), dtype=torch.uint8, device="cuda")
+    ctx = M.StreamCtx(L.cfg, L.host_packed, slots, slots_n)
+    for tokens_per_load in (16.0, 120.5, 4096.0):           # computation-heavy, mixed, load-dominated
+        ctx.set_order(M.ORDER_GREEDY, tokens_per_load, K)
+        L.y.fill_(float("nan"))
+        M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, None, ctx, L.y, L.ws)
+        torch.cuda.synchronize()
+        assert torch.equal(L.y, y_res)
+        live = [e for e, c in enumerate(counts) if c > 0]
+        want, want_ok = S.greedy_order([float(counts[e]) for e in live], tokens_per_load, K)
+        got, got_ok = ctx.last_order()
+        assert got == [live[i] for i in want] and got_ok == want_ok
+        assert len(got) == ctx.stats()["n_loaded"] == len(live) < wl.E
+    ctx.set_order(M.ORDER_ASCENDING)
+    M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, None, ctx, L.y, L.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(L.y, y_res) and ctx.last_order() == (live, False)
+    ctx.close()
