@@ -138,6 +138,29 @@ def route(x: np.ndarray, Wg: np.ndarray, k: int = 1, bias: Optional[np.ndarray] 
     return Routing(idx, w.astype(np.float32), L, margin)
 
 
+def route_hash(x: np.ndarray, Wh: np.ndarray) -> Routing:
+    """Sign-bit reading of Section 2.3's gate ("a random projection as a locality sensitive hashing
+    function"): the hidden state is projected on b random directions W_h[d, b] and the signs of the b
+    projections, read as a binary number, name one of E = 2^b experts:
+        idx[t] = sum_j [ x_t . W_h[:, j] > 0 ] * 2^j,        weight 1.
+    A projection that is exactly zero gives bit 0.  As in route(), the decision is the one exact
+    arithmetic gives: projections closer to zero than the matmul's error bound are re-evaluated with
+    exact_logits_row.  margin = the smallest |projection| of the token."""
+    x64 = np.asarray(x, dtype=np.float64)
+    W64 = np.asarray(Wh, dtype=np.float64)
+    L = gate_logits(x64, W64)
+    T, b = L.shape
+    if not 1 <= b <= 8:
+        raise ValueError("need 1 <= bits <= 8")
+    d = x64.shape[1]
+    col = np.sqrt((W64 * W64).sum(axis=0)).max()
+    bound = (d + 4) * 2.0 ** -53 * (np.sqrt((x64 * x64).sum(axis=1)) * col + np.abs(L).max(axis=1))
+    for t in np.nonzero(np.abs(L).min(axis=1) <= 4.0 * bound)[0]:
+        L[t] = exact_logits_row(x64[t], W64)
+    code = ((L > 0.0).astype(np.int64) << np.arange(b, dtype=np.int64)[None, :]).sum(axis=1)
+    return Routing(code.astype(np.int32)[:, None], np.ones((T, 1), dtype=np.float32), L, np.abs(L).min(axis=1))
+
+
 def permute(x: np.ndarray, idx: np.ndarray, E: int) -> Permutation:
     """Batch the assignments by expert (Section 6.2), keeping flat order a = t*k + j inside an expert."""
     T, k = idx.shape
@@ -186,6 +209,14 @@ def combine(Yp: np.ndarray, inv: np.ndarray, w: np.ndarray) -> np.ndarray:
     for j in range(k):
         y += w64[:, j:j + 1] * Yp[inv2[:, j]]
     return y
+
+
+def layer_forward_hash(x: np.ndarray, Wh: np.ndarray, experts: ExpertSource, act: int = 0):
+    """The layer with the sign-bit gate: route_hash -> permute -> expert FFNs -> combine (weights are 1)."""
+    r = route_hash(x, Wh)
+    p = permute(x, r.idx, 1 << np.asarray(Wh).shape[1])
+    Yp = expert_ffn(p.Xp, p.offsets, experts, act)
+    return combine(Yp, p.inv, r.w), r, p, Yp
 
 
 def layer_forward(x: np.ndarray, Wg: np.ndarray, experts: ExpertSource, E: int, k: int = 1,
