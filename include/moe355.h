@@ -42,6 +42,7 @@ extern "C" {
 
 enum { MOE_OK = 0, MOE_ERR_INVALID_ARG = -1, MOE_ERR_UNSUPPORTED = -2, MOE_ERR_WORKSPACE = -3, MOE_ERR_HIP = -4 };
 enum { MOE_F32 = 0, MOE_BF16 = 1 };
+enum { MOE_GATE_TOPK = 0, MOE_GATE_HASH = 1 };
 
 typedef struct moe_cfg {
     int32_t T;       /* tokens */
@@ -53,6 +54,10 @@ typedef struct moe_cfg {
     int32_t renorm;  /* 1: combine weights = softmax over the k selected logits (k = 1 -> exactly 1.0)
                         0: combine weights = full-softmax probability of each selected expert */
     int32_t act;     /* 0: exact GELU z*Phi(z);  1: tanh approximation of GELU */
+    int32_t gate;    /* MOE_GATE_TOPK: the k largest of the E projections x.W_g[:, e] (+ bias);
+                        MOE_GATE_HASH: the gate of Section 2.3 read literally as a locality sensitive hash:
+                        W_g is [d, log2 E], bit j of the expert id is set when x.W_g[:, j] > 0 (an exactly
+                        zero projection gives 0), weight 1; needs E a power of two >= 2, k = 1, no bias */
 } moe_cfg;
 
 typedef struct moe_stream_ctx moe_stream_ctx;   /* opaque: state of the host-streamed expert mode */

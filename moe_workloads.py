@@ -50,6 +50,7 @@ class Workload:
     zipf_s: Optional[float] = None   # skewed loads: per-expert gate bias
     n_dead: int = 0                  # experts whose bias guarantees zero tokens
     streamed: bool = False           # experts live in pinned host memory
+    gate: str = "topk"               # "topk": projection on E directions; "hash": sign bits of log2(E) projections
 
     @property
     def A(self) -> int:
@@ -159,7 +160,12 @@ def gen_x(wl: Workload, pool: Optional[ThreadPoolExecutor] = None) -> np.ndarray
 
 
 def gen_gate(wl: Workload) -> Tuple[np.ndarray, Optional[np.ndarray]]:
-    """Gate projection W_g[d, E] and, for skewed workloads, the bias b[E] (fp32)."""
+    """Gate projection W_g[d, E] and, for skewed workloads, the bias b[E] (fp32); for the hashing gate
+    W_g[d, log2 E] and no bias."""
+    if wl.gate == "hash":
+        bits = wl.E.bit_length() - 1
+        assert 1 << bits == wl.E and wl.k == 1 and wl.zipf_s is None
+        return _gaussian((wl.d, bits), wl.seed, _TID_WG, 0, 1.0 / np.sqrt(wl.d), wl.dtype), None
     Wg = _gaussian((wl.d, wl.E), wl.seed, _TID_WG, 0, 1.0 / np.sqrt(wl.d), wl.dtype)
     bias = None
     if wl.zipf_s is not None:

@@ -18,12 +18,12 @@ class MoeError(RuntimeError):
 
 class MoeCfg(C.Structure):
     _fields_ = [("T", C.c_int32), ("d", C.c_int32), ("f", C.c_int32), ("E", C.c_int32), ("k", C.c_int32),
-                ("dtype", C.c_int32), ("renorm", C.c_int32), ("act", C.c_int32)]
+                ("dtype", C.c_int32), ("renorm", C.c_int32), ("act", C.c_int32), ("gate", C.c_int32)]
 
     @classmethod
-    def make(cls, T, d, f, E, k=1, dtype="bf16", renorm=1, act=0) -> "MoeCfg":
+    def make(cls, T, d, f, E, k=1, dtype="bf16", renorm=1, act=0, gate=0) -> "MoeCfg":
         code = {"bf16": MOE_BF16, "f32": MOE_F32}[dtype] if isinstance(dtype, str) else int(dtype)
-        return cls(T, d, f, E, k, code, renorm, act)
+        return cls(T, d, f, E, k, code, renorm, act, gate)
 
     @property
     def torch_dtype(self):
@@ -175,6 +175,7 @@ def moe_layer_forward(cfg, x, W_g, gate_bias, W_packed, sctx: Optional[StreamCtx
 
 
 ORDER_ASCENDING, ORDER_GREEDY = 0, 1
+GATE_TOPK, GATE_HASH = 0, 1
 
 
 def moe_schedule_order(counts, tokens_per_load: float, K: int):

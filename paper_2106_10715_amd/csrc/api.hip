@@ -33,6 +33,9 @@ int check_cfg(const moe_cfg* c) {
     if (c->k < 1 || c->k > 8 || c->k > c->E) return fail(MOE_ERR_INVALID_ARG, "k must be in [1, min(E, 8)] (got %d)", c->k);
     if (c->renorm != 0 && c->renorm != 1) return fail(MOE_ERR_INVALID_ARG, "renorm must be 0 or 1");
     if (c->act != 0 && c->act != 1) return fail(MOE_ERR_INVALID_ARG, "act must be 0 (erf GELU) or 1 (tanh GELU)");
+    if (c->gate != MOE_GATE_TOPK && c->gate != MOE_GATE_HASH) return fail(MOE_ERR_INVALID_ARG, "gate must be MOE_GATE_TOPK or MOE_GATE_HASH");
+    if (c->gate == MOE_GATE_HASH && (c->E < 2 || (c->E & (c->E - 1)) != 0 || c->k != 1))
+        return fail(MOE_ERR_INVALID_ARG, "the hashing gate needs E a power of two >= 2 and k = 1 (got E = %d, k = %d)", c->E, c->k);
     const long long A = static_cast<long long>(c->T) * c->k;
     const long long widest = c->d > c->f ? c->d : c->f;
     if (A * widest >= (1LL << 31)) return fail(MOE_ERR_INVALID_ARG, "T*k*max(d,f) must stay below 2^31");
@@ -136,6 +139,8 @@ int moe_route(const moe_cfg* cfg, const void* x, const void* W_g, const float* g
     if (cfg->T == 0) return MOE_OK;
     REQUIRE(x, "x"); REQUIRE(idx, "idx"); REQUIRE(w, "w"); REQUIRE(ws, "ws");
     REQUIRE_ALIGNED(x, "x"); REQUIRE_ALIGNED(ws, "ws");
+    if (cfg->gate == MOE_GATE_HASH && gate_bias != nullptr)
+        return fail(MOE_ERR_INVALID_ARG, "the hashing gate takes no bias");
     return launch_route(*cfg, x, W_g, gate_bias, idx, w, static_cast<char*>(ws) + ws_layout(*cfg).route,
                         static_cast<hipStream_t>(stream));
 }
@@ -185,6 +190,8 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
     if (sctx != nullptr &&
         (sctx->cfg.d != cfg->d || sctx->cfg.f != cfg->f || sctx->cfg.E != cfg->E || sctx->cfg.dtype != cfg->dtype))
         return fail(MOE_ERR_INVALID_ARG, "stream context was created for another d/f/E/dtype");
+    if (cfg->gate == MOE_GATE_HASH && gate_bias != nullptr)
+        return fail(MOE_ERR_INVALID_ARG, "the hashing gate takes no bias");
     if (cfg->T == 0) return MOE_OK;
     REQUIRE(x, "x"); REQUIRE(y, "y"); REQUIRE(ws, "ws");
     REQUIRE_ALIGNED(x, "x"); REQUIRE_ALIGNED(y, "y");

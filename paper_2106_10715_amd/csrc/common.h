@@ -59,6 +59,8 @@ WsLayout ws_layout(const moe_cfg& c);
 // ---- launchers (each enqueues on `s` and returns MOE_OK or an error already recorded) ----
 // `scratch`: route_scratch_bytes(c) bytes of workspace (the gate re-packed for the matrix cores).
 size_t route_scratch_bytes(const moe_cfg& c);
+// Columns of the gate matrix: E for the projection gate, log2(E) sign bits for the hashing gate.
+int gate_columns(const moe_cfg& c);
 int launch_route(const moe_cfg& c, const void* x, const void* Wg, const float* bias, int32_t* idx, float* w,
                  void* scratch, hipStream_t s);
 int launch_permute(const moe_cfg& c, const void* x, const int32_t* idx, int32_t* counts, int32_t* offsets,

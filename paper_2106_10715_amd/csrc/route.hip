@@ -83,6 +83,23 @@ __device__ inline void emit_token(const double (&lv)[kNE], const double (&sv)[kS
     }
 }
 
+// Sign-bit gate (the gate of Section 2.3 read as a hashing function): column j of the projection gives
+// bit j of the expert id, set when the projection is positive.  Lane j < bits holds projection j in
+// lv[0].  gap = the smallest |projection| (how close the token is to a boundary), vmax = the largest.
+__device__ inline void sign_bits(const double (&lv)[kNE], int eg, bool owner, int bits, int& code, double& gap, double& vmax) {
+    const bool mine = owner && eg < bits;
+    const unsigned long long set = __ballot(mine && lv[0] > 0.0);
+    code = static_cast<int>(set & ((1ull << bits) - 1ull));
+    double lo = mine ? fabs(lv[0]) : INFINITY, hi = mine ? fabs(lv[0]) : 0.0;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        lo = fmin(lo, __shfl_xor(lo, off));
+        hi = fmax(hi, __shfl_xor(hi, off));
+    }
+    gap = lo;
+    vmax = hi;
+}
+
 // Smallest gap between consecutive ranks 0..kk-1 and the largest magnitude among them.
 __device__ inline void rank_gaps(const double (&sv)[kSel], int kk, double& gap, double& vmax) {
     gap = INFINITY;
@@ -98,7 +115,8 @@ template <typename XT>
 __global__ __launch_bounds__(kWaves * 64) void route_kernel(const XT* __restrict__ x, const XT* __restrict__ Wg,
                                                             const float* __restrict__ bias,
                                                             int32_t* __restrict__ idx, float* __restrict__ w,
-                                                            int T, int d, int E, int k, int renorm) {
+                                                            int T, int d, int E, int k, int renorm, int hash) {
+    // hash: E is the number of sign bits (columns of the projection), one expert id per token, weight 1
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int t0 = (blockIdx.x * kWaves + wave) * kTPW;
@@ -197,12 +215,16 @@ __global__ __launch_bounds__(kWaves * 64) void route_kernel(const XT* __restrict
         for (int i = 0; i < kNE; ++i) lv[i] = static_cast<double>(tot[tt][i] + bl[i]);
         double sv[kSel];
         int se[kSel];
-        wave_topk(lv, eg, owner, E, kk_sel, sv, se);
-
+        int code = 0;
+        double vmax, gap;
+        if (hash) {
+            sign_bits(lv, eg, owner, E, code, gap, vmax);
+        } else {
+            wave_topk(lv, eg, owner, E, kk_sel, sv, se);
+            rank_gaps(sv, kk_sel, gap, vmax);
+        }
         // |computed - exact| <= n_round u |x_t| |W_g col| + u |logit| for every logit that matters
         // (Cauchy-Schwarz bounds the sum of |products|); 1/16 of slack covers the fp32 norms themselves.
-        double vmax, gap;
-        rank_gaps(sv, kk_sel, gap, vmax);
         const double delta = 1.0625 * 5.9604644775390625e-8 *
                              (static_cast<double>(n_round) * sqrt(static_cast<double>(xsq[tt]) * static_cast<double>(wn2)) + vmax);
         if (gap <= 2.0 * delta) {
@@ -223,11 +245,15 @@ __global__ __launch_bounds__(kWaves * 64) void route_kernel(const XT* __restrict
                 for (int i = 0; i < kNE; ++i) acc[i] += __shfl_xor(acc[i], off);
 #pragma unroll
             for (int i = 0; i < kNE; ++i) lv[i] = acc[i] + static_cast<double>(bl[i]);
-            wave_topk(lv, eg, owner, E, kk_sel, sv, se);
+            if (hash) sign_bits(lv, eg, owner, E, code, gap, vmax);
+            else wave_topk(lv, eg, owner, E, kk_sel, sv, se);
         }
-
-        emit_token(lv, sv, se, eg, owner, E, k, renorm, lane, idx + static_cast<size_t>(t) * k,
-                   w + static_cast<size_t>(t) * k);
+        if (hash) {
+            if (lane == 0) { idx[t] = code; w[t] = 1.f; }
+        } else {
+            emit_token(lv, sv, se, eg, owner, E, k, renorm, lane, idx + static_cast<size_t>(t) * k,
+                       w + static_cast<size_t>(t) * k);
+        }
     }
 }
 
@@ -289,7 +315,9 @@ template <int NB>
 __global__ __launch_bounds__(256) void route_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wg,
                                                          const uint4* __restrict__ pack, const float* __restrict__ part,
                                                          const float* __restrict__ bias, int32_t* __restrict__ idx,
-                                                         float* __restrict__ w, int T, int d, int E, int k, int renorm) {
+                                                         float* __restrict__ w, int T, int d, int E, int k, int renorm,
+                                                         int hash) {
+    // hash: E is the number of sign bits (columns of the projection), one expert id per token, weight 1
     constexpr int EP = NB * 32;
     __shared__ float logit[kGateTokens][EP + 1];
     __shared__ float xsq_w[4][kGateTokens];
@@ -382,15 +410,25 @@ __global__ __launch_bounds__(256) void route_mfma_kernel(const uint16_t* __restr
         for (int i = 0; i < kNE; ++i) lv[i] = eg + 64 * i < E ? static_cast<double>(logit[tt][eg + 64 * i] + bl[i]) : 0.0;
         double sv[kSel];
         int se[kSel];
-        wave_topk(lv, eg, true, E, kk_sel, sv, se);
+        int code = 0;
         double gap, vmax;
-        rank_gaps(sv, kk_sel, gap, vmax);
+        if (hash) {
+            sign_bits(lv, eg, true, E, code, gap, vmax);
+        } else {
+            wave_topk(lv, eg, true, E, kk_sel, sv, se);
+            rank_gaps(sv, kk_sel, gap, vmax);
+        }
         const double xn2 = static_cast<double>(((xsq_w[0][tt] + xsq_w[1][tt]) + xsq_w[2][tt]) + xsq_w[3][tt]);
         const double delta = gamma * sqrt(xn2 * wn2) + 1.0625 * 5.9604644775390625e-8 * vmax;
         const bool close = gap <= 2.0 * delta;
         if (lane == 0) flagged[tt] = close ? 1 : 0;
-        if (!close)
-            emit_token(lv, sv, se, eg, true, E, k, renorm, lane, idx + static_cast<size_t>(t) * k, w + static_cast<size_t>(t) * k);
+        if (!close) {
+            if (hash) {
+                if (lane == 0) { idx[t] = code; w[t] = 1.f; }
+            } else {
+                emit_token(lv, sv, se, eg, true, E, k, renorm, lane, idx + static_cast<size_t>(t) * k, w + static_cast<size_t>(t) * k);
+            }
+        }
     }
     __syncthreads();
 
@@ -442,16 +480,30 @@ __global__ __launch_bounds__(256) void route_mfma_kernel(const uint16_t* __restr
                 const int ei = eg + 64 * i;
                 lv[i] = ei < E ? (((resc[0][ei] + resc[1][ei]) + resc[2][ei]) + resc[3][ei]) + static_cast<double>(bl[i]) : 0.0;
             }
-            double sv[kSel];
-            int se[kSel];
-            wave_topk(lv, eg, true, E, kk_sel, sv, se);
-            emit_token(lv, sv, se, eg, true, E, k, renorm, lane, idx + static_cast<size_t>(t) * k, w + static_cast<size_t>(t) * k);
+            if (hash) {
+                int code;
+                double gap, vmax;
+                sign_bits(lv, eg, true, E, code, gap, vmax);
+                if (lane == 0) { idx[t] = code; w[t] = 1.f; }
+            } else {
+                double sv[kSel];
+                int se[kSel];
+                wave_topk(lv, eg, true, E, kk_sel, sv, se);
+                emit_token(lv, sv, se, eg, true, E, k, renorm, lane, idx + static_cast<size_t>(t) * k, w + static_cast<size_t>(t) * k);
+            }
         }
         __syncthreads();
     }
 }
 
 }  // namespace
+
+int gate_columns(const moe_cfg& c) {
+    if (c.gate != MOE_GATE_HASH) return c.E;
+    int bits = 0;
+    while ((1 << bits) < c.E) ++bits;
+    return bits;
+}
 
 size_t route_scratch_bytes(const moe_cfg& c) {
     if (c.dtype != MOE_BF16) return 0;
@@ -462,19 +514,22 @@ size_t route_scratch_bytes(const moe_cfg& c) {
 int launch_route(const moe_cfg& c, const void* x, const void* Wg, const float* bias, int32_t* idx, float* w,
                  void* scratch, hipStream_t s) {
     if (c.T == 0) return MOE_OK;
+    const int hash = c.gate == MOE_GATE_HASH ? 1 : 0;
+    const int cols = gate_columns(c);          // columns of the gate matrix: experts, or sign bits
     if (c.dtype == MOE_BF16) {
-        const int NB = (c.E + 31) / 32;
+        const int NB = (cols + 31) / 32;
         const size_t EP = static_cast<size_t>(NB) * 32;
         uint4* pack = static_cast<uint4*>(scratch);
         float* part = reinterpret_cast<float*>(static_cast<char*>(scratch) + align256(EP * c.d * 2));
-        hipLaunchKernelGGL(gate_prep_kernel, dim3(c.d / 64), dim3(256), 0, s, static_cast<const uint16_t*>(Wg), c.d, c.E, NB,
+        hipLaunchKernelGGL(gate_prep_kernel, dim3(c.d / 64), dim3(256), 0, s, static_cast<const uint16_t*>(Wg), c.d, cols, NB,
                            pack, part);
         MOE_LAUNCH_CHECK("gate_prep_kernel");
         dim3 grid((c.T + kGateTokens - 1) / kGateTokens), block(256);
 #define MOE_ROUTE_CASE(N)                                                                                             \
     case N:                                                                                                           \
         hipLaunchKernelGGL(route_mfma_kernel<N>, grid, block, 0, s, static_cast<const uint16_t*>(x),                   \
-                           static_cast<const uint16_t*>(Wg), pack, part, bias, idx, w, c.T, c.d, c.E, c.k, c.renorm); \
+                           static_cast<const uint16_t*>(Wg), pack, part, bias, idx, w, c.T, c.d, cols, c.k, c.renorm, \
+                           hash);                                                                                     \
         break;
         switch (NB) {
             MOE_ROUTE_CASE(1) MOE_ROUTE_CASE(2) MOE_ROUTE_CASE(3) MOE_ROUTE_CASE(4)
@@ -488,7 +543,7 @@ int launch_route(const moe_cfg& c, const void* x, const void* Wg, const float* b
     const int per_block = kWaves * kTPW;
     dim3 grid((c.T + per_block - 1) / per_block), block(kWaves * 64);
     hipLaunchKernelGGL(route_kernel<float>, grid, block, 0, s, static_cast<const float*>(x),
-                       static_cast<const float*>(Wg), bias, idx, w, c.T, c.d, c.E, c.k, c.renorm);
+                       static_cast<const float*>(Wg), bias, idx, w, c.T, c.d, cols, c.k, c.renorm, hash);
     MOE_LAUNCH_CHECK("route_kernel");
     return MOE_OK;
 }

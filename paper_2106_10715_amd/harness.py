@@ -27,7 +27,7 @@ def to_f64(t: torch.Tensor) -> np.ndarray:
 
 
 def cfg_of(wl: W.Workload, act: int = 0) -> B.MoeCfg:
-    return B.MoeCfg.make(wl.T, wl.d, wl.f, wl.E, wl.k, wl.dtype, wl.renorm, act)
+    return B.MoeCfg.make(wl.T, wl.d, wl.f, wl.E, wl.k, wl.dtype, wl.renorm, act, B.GATE_HASH if wl.gate == "hash" else B.GATE_TOPK)
 
 
 @dataclass

@@ -20,6 +20,8 @@ def rel_l2(got, ref):
 def oracle_layer(wl, act=0):
     x = W.gen_x(wl)
     Wg, bias = W.gen_gate(wl)
+    if wl.gate == "hash":
+        return O.layer_forward_hash(x, Wg, lambda e: W.gen_expert(wl, e), act)
     return O.layer_forward(x, Wg, lambda e: W.gen_expert(wl, e), wl.E, wl.k, bias, wl.renorm, act)
 
 
@@ -50,6 +52,8 @@ MID = [
     W.Workload("mid-bf16-top2-zipf", T=900, d=192, f=320, E=12, k=2, dtype="bf16", seed=22, zipf_s=1.2, n_dead=3),
     W.Workload("mid-f32-top3-full", T=150, d=128, f=256, E=5, k=3, dtype="f32", seed=23, renorm=0),
     W.Workload("one-expert", T=130, d=128, f=128, E=1, k=1, dtype="bf16", seed=24),
+    W.Workload("hash-gate-bf16", T=600, d=256, f=384, E=8, k=1, dtype="bf16", seed=25, gate="hash"),
+    W.Workload("hash-gate-f32", T=90, d=128, f=256, E=4, k=1, dtype="f32", seed=26, gate="hash"),
 ]
 
 

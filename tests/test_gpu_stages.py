@@ -98,6 +98,60 @@ def test_route_ties_and_near_ties(dtype):
     assert (ref.margin < 1e-6).sum() >= 2
 
 
+@pytest.mark.parametrize("T,d,bits,dtype", [(64, 256, 2, "f32"), (257, 512, 5, "bf16"), (130, 192, 8, "bf16"),
+                                           (50, 64, 1, "bf16"), (33, 4096, 5, "bf16"), (77, 128, 6, "f32")])
+def test_hash_gate_matches_oracle(T, d, bits, dtype):
+    """Sign-bit gate: expert id = sign pattern of log2(E) projections, weight exactly 1 (integer result)."""
+    x, Wh, _ = make_inputs(300 + T + bits, T, d, bits, dtype)
+    cfg = M.MoeCfg.make(T, d, 64, 1 << bits, 1, dtype, gate=M.GATE_HASH)
+    idx, w = gpu_route(cfg, x, Wh, None, dtype)
+    ref = O.route_hash(x, Wh)
+    assert np.array_equal(idx, ref.idx), f"min oracle margin {ref.margin.min():.3e}"
+    assert np.all(w == 1.0)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_hash_gate_on_and_near_the_boundaries(dtype):
+    """Tokens exactly on a hyperplane (projection 0 -> bit 0), and tokens whose projection is far below what
+    fp32 accumulation resolves: both sides must take the exact sign."""
+    T, d, bits = 64, 256, 4
+    x, Wh, _ = make_inputs(9, T, d, bits, dtype)
+    x[5] = 0.0                                             # every projection exactly zero
+    Wh[:, 2] = 0.0
+    Wh[7, 2] = 1.0                                         # direction 2 reads coordinate 7
+    x[6, 7] = 0.0                                          # exactly on hyperplane 2
+    x[8, 7] = rounded(np.array([2.0 ** -100]), dtype)[0]   # barely on the positive side
+    x[9, 7] = -x[8, 7]
+    # a projection that cancels to a tiny value: direction 3 = (1, -1, 0, ...) on nearly equal coordinates
+    Wh[:, 3] = 0.0
+    Wh[0, 3], Wh[1, 3] = 1.0, -1.0
+    x[10, 0] = rounded(np.array([1.0 + 2.0 ** -7]), dtype)[0]
+    x[10, 1] = 1.0
+    x[11, 0], x[11, 1] = 1.0, x[10, 0]
+    x[12, 0] = x[12, 1] = 3.0                              # exact cancellation
+    cfg = M.MoeCfg.make(T, d, 64, 1 << bits, 1, dtype, gate=M.GATE_HASH)
+    idx, w = gpu_route(cfg, x, Wh, None, dtype)
+    ref = O.route_hash(x, Wh)
+    assert np.array_equal(idx, ref.idx)
+    assert idx[5, 0] == 0
+    assert (idx[6, 0] >> 2) & 1 == 0 and (idx[8, 0] >> 2) & 1 == 1 and (idx[9, 0] >> 2) & 1 == 0
+    assert (idx[10, 0] >> 3) & 1 == 1 and (idx[11, 0] >> 3) & 1 == 0 and (idx[12, 0] >> 3) & 1 == 0
+    assert np.all(w == 1.0)
+
+
+def test_hash_gate_rejects_what_it_cannot_take():
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    z = torch.zeros((8, 64), dtype=torch.bfloat16, device="cuda")
+    i = torch.zeros((8, 1), dtype=torch.int32, device="cuda")
+    wv = torch.zeros((8, 1), dtype=torch.float32, device="cuda")
+    b = torch.zeros(8, dtype=torch.float32, device="cuda")
+    for E, k in ((6, 1), (1, 1), (8, 2)):
+        with pytest.raises(M.MoeError):
+            M.moe_route(M.MoeCfg.make(8, 64, 64, E, k, "bf16", gate=M.GATE_HASH), z, z, None, i, wv, ws)
+    with pytest.raises(M.MoeError):
+        M.moe_route(M.MoeCfg.make(8, 64, 64, 8, 1, "bf16", gate=M.GATE_HASH), z, z, b, i, wv, ws)
+
+
 def test_route_dead_experts_get_nothing():
     T, d, E, k = 200, 128, 16, 2
     x, Wg, _ = make_inputs(6, T, d, E, "bf16")
