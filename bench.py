@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Throughput of the CPM-2-MoE feed-forward layer on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c5|c4a|c4b]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c5|c6|c4a|c4b]
 
 A step is one moe_layer_forward (route -> permute -> expert FFNs -> combine) over one batch of
 seeded synthetic tokens that is already resident in HBM.  Prints ONE JSON line: whole-layer
@@ -30,7 +30,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4a", "c4b", "c5"])
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4a", "c4b", "c5", "c6"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streamed", action="store_true", help="run the workload with host-streamed experts even if it is defined resident")
     ap.add_argument("--slots", type=int, default=2, help="device slots of the streamed mode")

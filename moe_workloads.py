@@ -60,7 +60,7 @@ class Workload:
         return replace(self, T=T, name=f"{self.name}-T{T}")
 
 
-# The five configurations the layer is measured on.  c1 is the small fp32 case a
+# The configurations the layer is measured on.  c1 is the small fp32 case a
 # CPU finishes instantly; c3 is the CPM-2-MoE layer of Table 1 with the 32 experts
 # of Section 6.2; c4a/c4b are the same layer with host-streamed experts; c5 is the
 # load-imbalance stress (the imbalance problem of Section 6.2).
@@ -74,6 +74,9 @@ CONFIGS = {
                     seed=1003, streamed=True),
     "c5": Workload("c5-zipf-E64-top2", T=16384, d=4096, f=10240, E=64, k=2, dtype="bf16",
                    seed=1005, zipf_s=1.2, n_dead=4),
+    # token-throughput regime: a fine-tuning batch of about 2^16 tokens (Section 4.1), 2048 tokens per
+    # expert, every expert bound by the matrix cores instead of by streaming its weights
+    "c6": Workload("c6-T65536-E32", T=65536, d=4096, f=10240, E=32, k=1, dtype="bf16", seed=1006),
 }
 
 # Bias of an expert that must receive no token at all.

@@ -259,8 +259,8 @@ __global__ __launch_bounds__(kWaves * 64) void route_kernel(const XT* __restrict
 
 // ------------------------------------------------------------------------------------------ bf16: MFMA gate
 //
-// logits tile = 32 tokens x E on 32x32x16 bf16 MFMAs.  The four waves of a block split the reduction
-// dimension (wave w takes the 64-element groups S = w, w+4, ...), the partial tiles are added in wave
+// logits tile = 32 tokens x E on 32x32x16 bf16 MFMAs.  The eight waves of a block split the reduction
+// dimension (wave w takes the 64-element groups S = w, w+8, ...), the partial tiles are added in wave
 // order through LDS.  W_g is first rewritten (gate_prep_kernel) into MFMA fragment order so that its
 // fragments are plain 1 KiB coalesced reads, and so that a lane's four fragments of a group use 64
 // contiguous bytes of its token row: fragment (nb, S, q), lane l, element j holds
@@ -274,6 +274,7 @@ __global__ __launch_bounds__(kWaves * 64) void route_kernel(const XT* __restrict
 // re-evaluated in fp64 by the whole block.
 
 constexpr int kGateTokens = 32;
+constexpr int kGateWaves = 8;    // waves of a gate block; they split the reduction dimension
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -312,7 +313,7 @@ __global__ __launch_bounds__(256) void gate_prep_kernel(const uint16_t* __restri
 }
 
 template <int NB>
-__global__ __launch_bounds__(256) void route_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wg,
+__global__ __launch_bounds__(kGateWaves * 64) void route_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wg,
                                                          const uint4* __restrict__ pack, const float* __restrict__ part,
                                                          const float* __restrict__ bias, int32_t* __restrict__ idx,
                                                          float* __restrict__ w, int T, int d, int E, int k, int renorm,
@@ -320,28 +321,44 @@ __global__ __launch_bounds__(256) void route_mfma_kernel(const uint16_t* __restr
     // hash: E is the number of sign bits (columns of the projection), one expert id per token, weight 1
     constexpr int EP = NB * 32;
     __shared__ float logit[kGateTokens][EP + 1];
-    __shared__ float xsq_w[4][kGateTokens];
+    __shared__ float xsq_w[kGateWaves][kGateTokens];
     __shared__ float wn2_sh;
     __shared__ int flagged[kGateTokens];
-    __shared__ double resc[4][EP];
+    __shared__ double resc[kGateWaves][EP];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int t0 = blockIdx.x * kGateTokens;
     const int nS = d / 64;
 
-    // ---- largest column norm of W_g: fixed-order sum of the per-group parts, then the block maximum
+    // ---- largest column norm of W_g: fixed-order sum of the per-group parts, then the block maximum.
+    // Thread (g, c) adds the parts S = g, g + G, ... of column c; thread c adds the G partial sums in order.
     {
+        __shared__ float colpart[kGateWaves * 64];
+        constexpr int G = EP >= kGateWaves * 64 ? 1 : kGateWaves * 64 / EP;
         float best = 0.f;
-        for (int c = threadIdx.x; c < EP; c += 256) {
+        for (int c0 = 0; c0 < EP; c0 += kGateWaves * 64) {          // one round unless EP exceeds the block
+            const int c = c0 + static_cast<int>(threadIdx.x) % EP, g = static_cast<int>(threadIdx.x) / EP;
             float ssum = 0.f;
-            for (int S = 0; S < nS; ++S) ssum += part[static_cast<size_t>(S) * EP + c];
-            best = fmaxf(best, ssum);
+            if (c < EP && g < G)
+                for (int S = g; S < nS; S += G) ssum += part[static_cast<size_t>(S) * EP + c];
+            colpart[threadIdx.x] = ssum;
+            __syncthreads();
+            if (g == 0 && c < EP) {
+                float tot = 0.f;
+                for (int gg = 0; gg < G; ++gg) tot += colpart[gg * EP + (c - c0)];
+                best = fmaxf(best, tot);
+            }
+            __syncthreads();
         }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) best = fmaxf(best, __shfl_xor(best, off));
         if (lane == 0) xsq_w[wave][0] = best;
         __syncthreads();
-        if (threadIdx.x == 0) wn2_sh = fmaxf(fmaxf(xsq_w[0][0], xsq_w[1][0]), fmaxf(xsq_w[2][0], xsq_w[3][0]));
+        if (threadIdx.x == 0) {
+            float m = xsq_w[0][0];
+            for (int wv = 1; wv < kGateWaves; ++wv) m = fmaxf(m, xsq_w[wv][0]);
+            wn2_sh = m;
+        }
         __syncthreads();
     }
 
@@ -354,10 +371,22 @@ __global__ __launch_bounds__(256) void route_mfma_kernel(const uint16_t* __restr
     const int row = min(t0 + (lane & 31), T - 1);
     const uint4* xrow = reinterpret_cast<const uint4*>(x + static_cast<size_t>(row) * d + 32 * (lane >> 5));
     float xs = 0.f;
-    for (int S = wave; S < nS; S += 4) {
-        uint4 xa[4];
+    // the loads of the next 64-element group are issued before the arithmetic of the current one
+    uint4 xa[4], wb[NB][4];
+    auto fetch = [&](int S, uint4 (&xv)[4], uint4 (&wv)[NB][4]) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) xa[q] = xrow[S * 8 + q];          // 64 contiguous bytes of the token row
+        for (int q = 0; q < 4; ++q) xv[q] = xrow[S * 8 + q];          // 64 contiguous bytes of the token row
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const uint4* bp = pack + ((static_cast<size_t>(nb) * nS + S) * 4) * 64 + lane;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) wv[nb][q] = bp[q * 64];
+        }
+    };
+    if (wave < nS) fetch(wave, xa, wb);
+    for (int S = wave; S < nS; S += kGateWaves) {
+        uint4 xn[4], wn[NB][4];
+        fetch(S + kGateWaves < nS ? S + kGateWaves : S, xn, wn);                        // past the end: the same group again, unused
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const uint32_t u[4] = {xa[q].x, xa[q].y, xa[q].z, xa[q].w};
@@ -369,18 +398,22 @@ __global__ __launch_bounds__(256) void route_mfma_kernel(const uint16_t* __restr
             }
         }
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const uint4* bp = pack + ((static_cast<size_t>(nb) * nS + S) * 4) * 64 + lane;
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
             for (int q = 0; q < 4; ++q)
                 acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[q]),
-                                                                   __builtin_bit_cast(bf16x8, bp[q * 64]), acc[nb], 0, 0, 0);
-        }
+                                                                   __builtin_bit_cast(bf16x8, wb[nb][q]), acc[nb], 0, 0, 0);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) xa[q] = xn[q];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) wb[nb][q] = wn[nb][q];
     }
     xs += __shfl_xor(xs, 32);
     if (lane < 32) xsq_w[wave][lane] = xs;
-    // partial tiles are added in wave order: ((w0 + w1) + w2) + w3
-    for (int turn = 0; turn < 4; ++turn) {
+    // partial tiles are added in wave order: ((w0 + w1) + w2) + ...
+    for (int turn = 0; turn < kGateWaves; ++turn) {
         if (wave == turn) {
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
@@ -394,7 +427,7 @@ __global__ __launch_bounds__(256) void route_mfma_kernel(const uint16_t* __restr
     }
 
     // ---- selection: wave w ranks tokens w, w+4, ...
-    const int n_chain = ((nS + 3) / 4) * 4;                               // MFMAs a wave chains per logit
+    const int n_chain = ((nS + kGateWaves - 1) / kGateWaves) * 4;                               // MFMAs a wave chains per logit
     const double gamma = 1.0625 * 5.9604644775390625e-8 * static_cast<double>(17 * n_chain + 8);
     const int eg = lane;
     const int kk_sel = min(k + 1, E);
@@ -402,7 +435,7 @@ __global__ __launch_bounds__(256) void route_mfma_kernel(const uint16_t* __restr
 #pragma unroll
     for (int i = 0; i < kNE; ++i) bl[i] = (bias != nullptr && eg + 64 * i < E) ? bias[eg + 64 * i] : 0.f;
     const double wn2 = static_cast<double>(wn2_sh);
-    for (int tt = wave; tt < kGateTokens; tt += 4) {
+    for (int tt = wave; tt < kGateTokens; tt += kGateWaves) {
         const int t = t0 + tt;
         if (t >= T) { if (lane == 0) flagged[tt] = 0; continue; }
         double lv[kNE];
@@ -418,7 +451,9 @@ __global__ __launch_bounds__(256) void route_mfma_kernel(const uint16_t* __restr
             wave_topk(lv, eg, true, E, kk_sel, sv, se);
             rank_gaps(sv, kk_sel, gap, vmax);
         }
-        const double xn2 = static_cast<double>(((xsq_w[0][tt] + xsq_w[1][tt]) + xsq_w[2][tt]) + xsq_w[3][tt]);
+        float xn2f = xsq_w[0][tt];
+        for (int wv = 1; wv < kGateWaves; ++wv) xn2f += xsq_w[wv][tt];
+        const double xn2 = static_cast<double>(xn2f);
         const double delta = gamma * sqrt(xn2 * wn2) + 1.0625 * 5.9604644775390625e-8 * vmax;
         const bool close = gap <= 2.0 * delta;
         if (lane == 0) flagged[tt] = close ? 1 : 0;
@@ -434,8 +469,8 @@ __global__ __launch_bounds__(256) void route_mfma_kernel(const uint16_t* __restr
 
     // ---- fp64 re-evaluation of the tokens that were too close to call, by the whole block, from the
     // same packed fragments and with the same split as the MFMA pass: wave w takes the groups
-    // S = w, w+4, ..., lane (c, h) the 32 rows 64 S + 32 h .. of column c of every expert block; the two
-    // halves are added by a lane exchange, the four waves in wave order.
+    // S = w, w+8, ..., lane (c, h) the 32 rows 64 S + 32 h .. of column c of every expert block; the two
+    // halves are added by a lane exchange, the waves in wave order.
     for (int tt = 0; tt < kGateTokens; ++tt) {
         if (!flagged[tt]) continue;                                      // uniform for the block
         const int t = t0 + tt;
@@ -443,7 +478,7 @@ __global__ __launch_bounds__(256) void route_mfma_kernel(const uint16_t* __restr
         double a64[NB];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) a64[nb] = 0.0;
-        for (int S = wave; S < nS; S += 4) {
+        for (int S = wave; S < nS; S += kGateWaves) {
             uint4 xa[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) xa[q] = xr[S * 8 + q];
@@ -478,7 +513,9 @@ __global__ __launch_bounds__(256) void route_mfma_kernel(const uint16_t* __restr
 #pragma unroll
             for (int i = 0; i < kNE; ++i) {
                 const int ei = eg + 64 * i;
-                lv[i] = ei < E ? (((resc[0][ei] + resc[1][ei]) + resc[2][ei]) + resc[3][ei]) + static_cast<double>(bl[i]) : 0.0;
+                double sum = ei < E ? resc[0][ei] : 0.0;
+                for (int wv = 1; wv < kGateWaves; ++wv) sum += ei < E ? resc[wv][ei] : 0.0;
+                lv[i] = ei < E ? sum + static_cast<double>(bl[i]) : 0.0;
             }
             if (hash) {
                 int code;
@@ -524,7 +561,7 @@ int launch_route(const moe_cfg& c, const void* x, const void* Wg, const float* b
         hipLaunchKernelGGL(gate_prep_kernel, dim3(c.d / 64), dim3(256), 0, s, static_cast<const uint16_t*>(Wg), c.d, cols, NB,
                            pack, part);
         MOE_LAUNCH_CHECK("gate_prep_kernel");
-        dim3 grid((c.T + kGateTokens - 1) / kGateTokens), block(256);
+        dim3 grid((c.T + kGateTokens - 1) / kGateTokens), block(kGateWaves * 64);
 #define MOE_ROUTE_CASE(N)                                                                                             \
     case N:                                                                                                           \
         hipLaunchKernelGGL(route_mfma_kernel<N>, grid, block, 0, s, static_cast<const uint16_t*>(x),                   \

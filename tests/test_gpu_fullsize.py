@@ -146,3 +146,13 @@ def test_c5_zipf_top2_full_size():
     assert counts.max() > 20 * max(1, counts[counts > 0].min())      # the load really is skewed
     del L
     torch.cuda.empty_cache()
+
+
+def test_c6_token_throughput_regime_full_size():
+    wl = W.CONFIGS["c6"]
+    L = H.build_layer(wl)
+    s = check_full_size(wl, L, n_experts=3)
+    counts = s["counts"].cpu().numpy()
+    assert counts.min() > 1500                                       # every expert is in the compute-bound regime
+    del L
+    torch.cuda.empty_cache()
