@@ -213,6 +213,16 @@ int moe_stage_timing_enable(int32_t max_calls);
 int moe_stage_timing_read(float* ms, int32_t capacity_calls, int32_t* n_calls);
 int moe_stage_timing_disable(void);
 
+/*
+ * The same for the dominant kernel alone: only two events per call, right before and right after the
+ * expert up-projection kernel of resident bf16 calls (an event between two kernels costs a few
+ * microseconds of idle time, so timing every stage slows the call it measures).
+ * moe_up_kernel_timing_read writes ms[call] (host, at most capacity_calls values).  Shares its state
+ * with the per-stage timing: enabling one replaces the other, moe_stage_timing_disable ends both.
+ */
+int moe_up_kernel_timing_enable(int32_t max_calls);
+int moe_up_kernel_timing_read(float* ms, int32_t capacity_calls, int32_t* n_calls);
+
 #ifdef __cplusplus
 }
 #endif

@@ -65,6 +65,8 @@ def lib() -> C.CDLL:
             "moe_stage_timing_enable": [C.c_int32],
             "moe_stage_timing_read": [C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)],
             "moe_stage_timing_disable": [],
+            "moe_up_kernel_timing_enable": [C.c_int32],
+            "moe_up_kernel_timing_read": [C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)],
         }
         for name, args in sigs.items():
             fn = getattr(L, name)
@@ -202,6 +204,18 @@ def moe_stage_timing_read(max_calls: int):
     _check(lib().moe_stage_timing_read(buf, max_calls, C.byref(n)))
     got = min(n.value, max_calls)
     return [{s: buf[c * len(STAGES) + i] for i, s in enumerate(STAGES)} for c in range(got)]
+
+
+def moe_up_kernel_timing_enable(max_calls: int) -> None:
+    _check(lib().moe_up_kernel_timing_enable(max_calls))
+
+
+def moe_up_kernel_timing_read(max_calls: int):
+    """List of per-call durations of the expert up-projection kernel in ms."""
+    buf = (C.c_float * max_calls)()
+    n = C.c_int32(0)
+    _check(lib().moe_up_kernel_timing_read(buf, max_calls, C.byref(n)))
+    return [buf[c] for c in range(min(n.value, max_calls))]
 
 
 def moe_stage_timing_disable() -> None:

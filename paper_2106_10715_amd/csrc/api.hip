@@ -95,6 +95,7 @@ namespace {
 constexpr int kStageEvents = 6;   // before route, after route, permute, up, down, combine
 struct StageTimer {
     bool on = false;
+    bool up_only = false;         // only the two events around the up-projection kernel
     int cap = 0, n = 0;
     hipEvent_t* ev = nullptr;
 } g_timer;
@@ -213,19 +214,21 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
 
     hipEvent_t* tev = nullptr;     // this call's stage events, if stage timing is on and has room
     if (sctx == nullptr && g_timer.on && g_timer.n < g_timer.cap) tev = g_timer.ev + kStageEvents * g_timer.n++;
-    if (tev) MOE_HIP_CHECK(hipEventRecord(tev[0], s));
+    const bool all_stages = tev != nullptr && !g_timer.up_only;
+    if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[0], s));
     if (int rc = launch_route(c, x, W_g, gate_bias, idx, w, base + L.route, s)) return rc;
-    if (tev) MOE_HIP_CHECK(hipEventRecord(tev[1], s));
+    if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[1], s));
     if (int rc = launch_permute(c, x, idx, counts, offsets, perm, inv, base + L.Xp,
                                 reinterpret_cast<int32_t*>(base + L.chunk_hist), s))
         return rc;
-    if (tev) MOE_HIP_CHECK(hipEventRecord(tev[2], s));
+    if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[2], s));
 
     if (sctx == nullptr) {
         if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, 0, c.E, W_packed, eb, A, base + L.H, base + L.Yp,
-                                       reinterpret_cast<int32_t*>(base + L.ffn_plan), s, tev ? tev[3] : nullptr))
+                                       reinterpret_cast<int32_t*>(base + L.ffn_plan), s, tev ? tev[3] : nullptr,
+                                       tev && g_timer.up_only ? tev[2] : nullptr))
             return rc;
-        if (tev) MOE_HIP_CHECK(hipEventRecord(tev[4], s));
+        if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[4], s));
     } else {
         // The host has to know which experts hold tokens (and how many) before it can queue loads.
         MOE_HIP_CHECK(hipMemcpyAsync(sctx->h_counts, counts, sizeof(int32_t) * c.E, hipMemcpyDeviceToHost, s));
@@ -265,7 +268,7 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
         sctx->timed = i > 0;
     }
     if (int rc = launch_combine(c, base + L.Yp, inv, w, y, s)) return rc;
-    if (tev) MOE_HIP_CHECK(hipEventRecord(tev[5], s));
+    if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[5], s));
     return MOE_OK;
 }
 
@@ -288,8 +291,29 @@ int moe_stage_timing_enable(int32_t max_calls) {
     return MOE_OK;
 }
 
+int moe_up_kernel_timing_enable(int32_t max_calls) {
+    if (int rc = moe_stage_timing_enable(max_calls)) return rc;
+    g_timer.up_only = true;
+    return MOE_OK;
+}
+
+int moe_up_kernel_timing_read(float* ms, int32_t capacity_calls, int32_t* n_calls) {
+    REQUIRE(n_calls, "n_calls");
+    if (!g_timer.up_only) return fail(MOE_ERR_INVALID_ARG, "moe_up_kernel_timing_enable was not called");
+    *n_calls = g_timer.n;
+    if (ms == nullptr) return MOE_OK;
+    const int n = g_timer.n < capacity_calls ? g_timer.n : capacity_calls;
+    for (int c = 0; c < n; ++c) {
+        hipEvent_t* ev = g_timer.ev + kStageEvents * c;
+        MOE_HIP_CHECK(hipEventSynchronize(ev[3]));
+        MOE_HIP_CHECK(hipEventElapsedTime(&ms[c], ev[2], ev[3]));
+    }
+    return MOE_OK;
+}
+
 int moe_stage_timing_read(float* ms, int32_t capacity_calls, int32_t* n_calls) {
     REQUIRE(n_calls, "n_calls");
+    if (g_timer.up_only) return fail(MOE_ERR_INVALID_ARG, "only the up-projection kernel is being timed");
     *n_calls = g_timer.n;
     if (ms == nullptr) return MOE_OK;
     const int n = g_timer.n < capacity_calls ? g_timer.n : capacity_calls;

@@ -69,10 +69,11 @@ int launch_pack(const moe_cfg& c, const void* Win, const void* Wgate, const void
 // Runs the FFN of experts [e_first, e_first + e_count); W points at the packed block of e_first and
 // consecutive experts are expert_stride_bytes apart.  max_rows bounds the rows those experts can hold
 // (it sizes the grid; blocks past the real row count exit).
-// `between`, if not null, is recorded on `s` after the up kernel and before the down kernel.
+// `between`, if not null, is recorded on `s` after the up kernel and before the down kernel;
+// `before_up`, if not null, right before the up kernel.
 int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, int e_first, int e_count,
                       const void* W, size_t expert_stride_bytes, long max_rows, void* H, void* Yp, int32_t* plan,
-                      hipStream_t s, hipEvent_t between = nullptr);
+                      hipStream_t s, hipEvent_t between = nullptr, hipEvent_t before_up = nullptr);
 // `plan`: ffn_plan_bytes(c) bytes of workspace, rewritten by every launch_expert_ffn (room for ffn_plan_tiles(c) row tiles).
 size_t ffn_plan_tiles(const moe_cfg& c);
 size_t ffn_plan_bytes(const moe_cfg& c);

@@ -501,17 +501,22 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
     }
     n[t] = cnt;
     first[t] = lo;
+    order[t] = t;
+    tl[t] = 0;
     __syncthreads();
-    int rank = 0;                       // more rows first, equal counts by expert index: a permutation of 0..255
-    for (int u = 0; u < 256; ++u) rank += (n[u] > cnt || (n[u] == cnt && u < t)) ? 1 : 0;
-    order[rank] = t;
+    if (t < e_count) {
+        int rank = 0;                   // more rows first, equal counts by expert index: a permutation of 0..e_count-1
+        for (int u = 0; u < e_count; ++u) rank += (n[u] > cnt || (n[u] == cnt && u < t)) ? 1 : 0;
+        order[rank] = t;
+    }
     __syncthreads();
-    const int mine = order[t], my_n = n[mine];
+    const int mine = order[t], my_n = t < e_count ? n[mine] : 0;
     const int my_tiles = (my_n + tile_m - 1) / tile_m;
     tl[t] = my_tiles;
     __syncthreads();
     int start = 0;
-    for (int r = 0; r < t; ++r) start += tl[r];
+    const int upto = t < e_count ? t : e_count;
+    for (int r = 0; r < upto; ++r) start += tl[r];
     if (my_tiles > 0) {
         const int per_tile = min(tile_m, ((my_n + my_tiles - 1) / my_tiles + 31) & ~31);
         int4* tiles = reinterpret_cast<int4*>(plan + kPlanHeader);
@@ -715,7 +720,7 @@ int launch_pack(const moe_cfg& c, const void* Win, const void* Wgate, const void
 
 int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, int e_first, int e_count,
                       const void* W, size_t expert_stride_bytes, long max_rows, void* H, void* Yp, int32_t* plan,
-                      hipStream_t s, hipEvent_t between) {
+                      hipStream_t s, hipEvent_t between, hipEvent_t before_up) {
     if (max_rows <= 0 || e_count <= 0) return MOE_OK;
     const size_t df = static_cast<size_t>(c.d) * c.f;
     if (c.dtype == MOE_BF16) {
@@ -739,6 +744,7 @@ int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, 
         auto grid_for = [&](long items) { return dim3(static_cast<unsigned>(items < n_cu ? items : n_cu)); };
         hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, s, offsets, e_first, e_count, kTileM, plan);
         MOE_LAUNCH_CHECK("ffn_plan_kernel");
+        if (before_up != nullptr) MOE_HIP_CHECK(hipEventRecord(before_up, s));
         const size_t down_off = 2 * df * 2;
         dim3 block(256);
         int yc = 0;
