@@ -147,7 +147,7 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
 /*
  * Streamed-mode state (Section 6.2: K experts resident at once, separate streams for loading and
  * computing).  host_experts: pinned, E packed experts back to back, expert_bytes each (must equal
- * moe_expert_bytes).  dev_slots: device, K * expert_bytes, 256-byte aligned.  1 <= K <= 16.
+ * moe_expert_bytes).  dev_slots: device, K * expert_bytes, 256-byte aligned.  1 <= K <= 64.
  * Both buffers stay owned by the caller and must outlive the context.  Must be called with the
  * device that holds dev_slots current.
  */
@@ -192,6 +192,39 @@ int moe_stream_ctx_set_order(moe_stream_ctx* sctx, int32_t policy, double tokens
  * *n_order experts; *satisfiable (may be NULL) as in moe_schedule_order, 0 for MOE_ORDER_ASCENDING.
  */
 int moe_stream_ctx_last_order(const moe_stream_ctx* sctx, int32_t* order, int32_t* n_order, int32_t* satisfiable);
+
+/*
+ * Experts that stay resident (Section 6.2: K experts can reside in GPU memory; K "configured or
+ * automatically inferred").
+ *
+ * moe_stream_slots_that_fit: the K a context can be given on the current device: how many packed experts
+ * of this cfg fit into the free device memory minus reserve_bytes, at most 64 and at most E.
+ *
+ * moe_stream_ctx_keep_experts(sctx, 1): from now on the slots keep their experts between calls; a
+ * streamed moe_layer_forward loads only the experts of its order that no slot holds.  Since the whole
+ * order of a call is known before its first load, the expert that gives way is the one whose next use
+ * in this call lies furthest ahead (an empty slot first; never used again before used later; among
+ * equals the slot unused for longest, then the lowest slot), which minimises the loads of the call.
+ * With K >= E every expert has its own slot, is loaded once, and a call that needs no load runs all its
+ * experts in one grouped launch, i.e. at the resident speed.  The host
+ * copy of the experts must not change while experts are kept; (sctx, 0) forgets what the slots hold
+ * and returns to loading every expert in every call (the default, which is what the measured
+ * streamed configurations do).  moe_stream_ctx_stats reports the experts actually copied.
+ *
+ * moe_stream_ctx_prefetch(sctx, e): start loading expert e into a slot now, on the copy stream, unless a
+ * slot holds it (needs keeping switched on).  Meant for a stack of layers: while layer l computes, the
+ * caller prefetches the expert it expects layer l+1 to run first, so that "no expert waits for its
+ * parameters except the first" holds once per model rather than once per layer.  Returns at once.
+ *
+ * moe_plan_slots is the replacement rule itself as a pure host function (all arrays host memory):
+ *   order [n] experts in execution order;  slot_expert [K] in/out, -1 = empty;  slot_tick [K] in/out, when
+ *   each slot was last used;  *tick in/out use counter;  slot_of [n], load [n] (1 = must be loaded) out.
+ */
+int moe_stream_slots_that_fit(const moe_cfg* cfg, size_t reserve_bytes, int32_t* K);
+int moe_stream_ctx_keep_experts(moe_stream_ctx* sctx, int32_t on);
+int moe_stream_ctx_prefetch(moe_stream_ctx* sctx, int32_t expert);
+int moe_plan_slots(const int32_t* order, int32_t n, int32_t K, int32_t* slot_expert, int64_t* slot_tick, int64_t* tick,
+                   int32_t* slot_of, int32_t* load);
 
 /*
  * Figures of the last streamed moe_layer_forward on this context; waits for that call's work to

@@ -90,3 +90,40 @@ def greedy_order(alpha: Sequence[float], beta: float, K: int) -> Tuple[List[int]
         chosen_sum += alpha[pick]
     covered, bounded = constraints_hold([alpha[i] for i in order], beta, K)
     return order, covered and bounded
+
+
+# ---------------------------------------------------------------------------------- resident experts
+#
+# Section 6.2: "only the parameters of a certain number (denoted as K ...) of experts can reside in GPU
+# memory simultaneously".  When K slots outlive a call, an expert that is still resident need not be
+# loaded again.  Which resident expert gives way when a slot is needed is not the paper's subject; the
+# reading used here: the whole execution order of a call is known before its first load, so the expert
+# whose next use in this call lies furthest ahead goes (never used again = furthest of all; among those
+# the one unused for longest, then the lowest slot) - the classical optimal replacement for a known
+# request sequence, which minimises the loads of the call.
+
+def plan_slots(order: Sequence[int], slot_expert: Sequence[int], slot_tick: Sequence[int], tick: int):
+    """For each position of `order`: (slot, load?) given the experts the K slots hold (-1 = empty) and when
+    each slot was last used.  Returns (slots, loads, slot_expert_after, slot_tick_after, tick_after)."""
+    held = list(slot_expert)
+    used = list(slot_tick)
+    slots, loads = [], []
+    for pos, e in enumerate(order):
+        if e in held:
+            s = held.index(e)
+            loads.append(False)
+        else:
+            def next_use(x):
+                for j in range(pos + 1, len(order)):
+                    if order[j] == x:
+                        return j
+                return len(order) + 1                      # never again in this call
+            # empty slots first, then furthest next use, then least recently used, then lowest slot
+            s = min(range(len(held)),
+                    key=lambda i: (0 if held[i] < 0 else 1, -(next_use(held[i]) if held[i] >= 0 else 0), used[i], i))
+            held[s] = e
+            loads.append(True)
+        tick += 1
+        used[s] = tick
+        slots.append(s)
+    return slots, loads, held, used, tick

@@ -62,6 +62,11 @@ def lib() -> C.CDLL:
                                    C.POINTER(C.c_int32), C.POINTER(C.c_int32)],
             "moe_stream_ctx_set_order": [p, C.c_int32, C.c_double, C.c_int32],
             "moe_stream_ctx_last_order": [p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)],
+            "moe_stream_slots_that_fit": [C.POINTER(MoeCfg), C.c_size_t, C.POINTER(C.c_int32)],
+            "moe_stream_ctx_keep_experts": [p, C.c_int32],
+            "moe_stream_ctx_prefetch": [p, C.c_int32],
+            "moe_plan_slots": [C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int64),
+                               C.POINTER(C.c_int64), C.POINTER(C.c_int32), C.POINTER(C.c_int32)],
             "moe_stage_timing_enable": [C.c_int32],
             "moe_stage_timing_read": [C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)],
             "moe_stage_timing_disable": [],
@@ -153,6 +158,12 @@ class StreamCtx:
     def set_order(self, policy: int, tokens_per_load: float = 1.0, K: int = 0) -> None:
         _check(lib().moe_stream_ctx_set_order(self._h, policy, tokens_per_load, K))
 
+    def keep_experts(self, on: bool = True) -> None:
+        _check(lib().moe_stream_ctx_keep_experts(self._h, 1 if on else 0))
+
+    def prefetch(self, expert: int) -> None:
+        _check(lib().moe_stream_ctx_prefetch(self._h, int(expert)))
+
     def last_order(self):
         order = (C.c_int32 * 256)()
         n, ok = C.c_int32(0), C.c_int32(0)
@@ -188,6 +199,24 @@ def moe_schedule_order(counts, tokens_per_load: float, K: int):
     n, ok = C.c_int32(0), C.c_int32(0)
     _check(lib().moe_schedule_order(c, E, float(tokens_per_load), int(K), order, C.byref(n), C.byref(ok)))
     return list(order[:n.value]), bool(ok.value)
+
+
+def moe_plan_slots(order, slot_expert, slot_tick, tick: int):
+    """(slot_of, load, slot_expert_after, slot_tick_after, tick_after); argument marshalling only."""
+    n, K = len(order), len(slot_expert)
+    o = (C.c_int32 * max(n, 1))(*[int(v) for v in order])
+    se = (C.c_int32 * K)(*[int(v) for v in slot_expert])
+    st = (C.c_int64 * K)(*[int(v) for v in slot_tick])
+    tk = C.c_int64(int(tick))
+    so, ld = (C.c_int32 * max(n, 1))(), (C.c_int32 * max(n, 1))()
+    _check(lib().moe_plan_slots(o, n, K, se, st, C.byref(tk), so, ld))
+    return list(so[:n]), [bool(v) for v in ld[:n]], list(se), list(st), tk.value
+
+
+def moe_stream_slots_that_fit(cfg: MoeCfg, reserve_bytes: int = 0) -> int:
+    K = C.c_int32(0)
+    _check(lib().moe_stream_slots_that_fit(C.byref(cfg), int(reserve_bytes), C.byref(K)))
+    return K.value
 
 
 STAGES = ("route", "permute", "ffn_up", "ffn_down", "combine")

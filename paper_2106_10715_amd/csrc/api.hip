@@ -68,6 +68,8 @@ WsLayout ws_layout(const moe_cfg& c) {
 
 using namespace moe;
 
+constexpr int kMaxSlots = 64;
+
 struct moe_stream_ctx {
     moe_cfg cfg;
     const char* host_experts;
@@ -76,9 +78,14 @@ struct moe_stream_ctx {
     int K;
     int device;
     hipStream_t copy_stream;
-    hipEvent_t loaded[16];     // copy into slot s finished
-    hipEvent_t released[16];   // compute that read slot s finished
-    bool released_valid[16];
+    hipEvent_t loaded[kMaxSlots];     // copy into slot s finished
+    hipEvent_t released[kMaxSlots];   // compute that read slot s finished
+    bool released_valid[kMaxSlots];
+    bool keep;                        // slots keep their experts between calls
+    int32_t slot_expert[kMaxSlots];   // expert held by each slot, -1 = none (only meaningful with keep)
+    int64_t slot_tick[kMaxSlots];     // when each slot was last used
+    int64_t tick;
+    int n_order;                      // experts run by the last call
     hipEvent_t first_copy, last_copy;
     bool timed;
     int32_t* h_counts;         // pinned [256]
@@ -243,29 +250,72 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
             for (int e = 0; e < c.E; ++e)
                 if (sctx->h_counts[e] > 0) sctx->order[n_order++] = e;
         }
+        // which slot each expert runs from, and whether it must be loaded: round-robin and always, unless the
+        // slots keep their experts between calls
+        int32_t slot_of[256], load[256];
+        const bool all_fit = sctx->keep && sctx->K >= c.E;     // every expert has its own slot: slot e holds expert e
+        if (all_fit) {
+            for (int pos = 0; pos < n_order; ++pos) {
+                const int e = sctx->order[pos];
+                slot_of[pos] = e;
+                load[pos] = sctx->slot_expert[e] == e ? 0 : 1;
+                sctx->slot_expert[e] = e;
+                sctx->slot_tick[e] = ++sctx->tick;
+            }
+        } else if (sctx->keep) {
+            if (int rc = plan_slots(sctx->order, n_order, sctx->K, sctx->slot_expert, sctx->slot_tick, &sctx->tick, slot_of, load))
+                return rc;
+        } else {
+            for (int pos = 0; pos < n_order; ++pos) { slot_of[pos] = pos % sctx->K; load[pos] = 1; }
+        }
+        int to_load = 0;
+        for (int pos = 0; pos < n_order; ++pos) to_load += load[pos];
+        if (all_fit && to_load == 0 && n_order > 0) {
+            // Everything this call needs is resident and the slots are laid out like a resident expert array:
+            // one launch over all experts instead of one per expert.
+            for (int pos = 0; pos < n_order; ++pos) MOE_HIP_CHECK(hipStreamWaitEvent(s, sctx->loaded[slot_of[pos]], 0));
+            if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, 0, c.E, sctx->dev_slots, eb, A, base + L.H, base + L.Yp,
+                                           reinterpret_cast<int32_t*>(base + L.ffn_plan), s))
+                return rc;
+            for (int pos = 0; pos < n_order; ++pos) {
+                MOE_HIP_CHECK(hipEventRecord(sctx->released[slot_of[pos]], s));
+                sctx->released_valid[slot_of[pos]] = true;
+            }
+            sctx->n_order = n_order;
+            sctx->n_loaded = 0;
+            sctx->timed = false;
+            n_order = 0;                                        // nothing left for the per-expert loop
+        } else {
+            sctx->n_order = n_order;
+        }
+        const bool grouped = n_order == 0 && sctx->n_order > 0 && all_fit;
         int i = 0;
         for (int pos = 0; pos < n_order; ++pos) {
             const int e = sctx->order[pos];
             const int n_e = sctx->h_counts[e];
-            const int slot = i % sctx->K;
+            const int slot = slot_of[pos];
             char* dst = sctx->dev_slots + static_cast<size_t>(slot) * eb;
-            // the load may not overwrite a slot an earlier expert (of this or the previous call) still reads
-            if (sctx->released_valid[slot]) MOE_HIP_CHECK(hipStreamWaitEvent(sctx->copy_stream, sctx->released[slot], 0));
-            if (i == 0) MOE_HIP_CHECK(hipEventRecord(sctx->first_copy, sctx->copy_stream));
-            MOE_HIP_CHECK(hipMemcpyAsync(dst, sctx->host_experts + static_cast<size_t>(e) * eb, eb, hipMemcpyHostToDevice,
-                                         sctx->copy_stream));
-            MOE_HIP_CHECK(hipEventRecord(sctx->loaded[slot], sctx->copy_stream));
-            MOE_HIP_CHECK(hipStreamWaitEvent(s, sctx->loaded[slot], 0));
+            if (load[pos]) {
+                // the load may not overwrite a slot an earlier expert (of this or a previous call) still reads
+                if (sctx->released_valid[slot]) MOE_HIP_CHECK(hipStreamWaitEvent(sctx->copy_stream, sctx->released[slot], 0));
+                if (i == 0) MOE_HIP_CHECK(hipEventRecord(sctx->first_copy, sctx->copy_stream));
+                MOE_HIP_CHECK(hipMemcpyAsync(dst, sctx->host_experts + static_cast<size_t>(e) * eb, eb, hipMemcpyHostToDevice,
+                                             sctx->copy_stream));
+                MOE_HIP_CHECK(hipEventRecord(sctx->loaded[slot], sctx->copy_stream));
+                ++i;
+            }
+            MOE_HIP_CHECK(hipStreamWaitEvent(s, sctx->loaded[slot], 0));   // also when kept: its load may still be running
             if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, e, 1, dst, eb, n_e, base + L.H, base + L.Yp,
                                            reinterpret_cast<int32_t*>(base + L.ffn_plan), s))
                 return rc;
             MOE_HIP_CHECK(hipEventRecord(sctx->released[slot], s));
             sctx->released_valid[slot] = true;
-            ++i;
         }
-        if (i > 0) MOE_HIP_CHECK(hipEventRecord(sctx->last_copy, sctx->copy_stream));
-        sctx->n_loaded = i;
-        sctx->timed = i > 0;
+        if (!grouped) {
+            if (i > 0) MOE_HIP_CHECK(hipEventRecord(sctx->last_copy, sctx->copy_stream));
+            sctx->n_loaded = i;
+            sctx->timed = i > 0;
+        }
     }
     if (int rc = launch_combine(c, base + L.Yp, inv, w, y, s)) return rc;
     if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[5], s));
@@ -342,7 +392,7 @@ int moe_stream_ctx_create(const moe_cfg* cfg, const void* host_experts, size_t e
     REQUIRE(out, "out");
     *out = nullptr;
     REQUIRE(host_experts, "host_experts"); REQUIRE(dev_slots, "dev_slots");
-    if (K < 1 || K > 16) return fail(MOE_ERR_INVALID_ARG, "K must be in [1, 16] (got %d)", K);
+    if (K < 1 || K > kMaxSlots) return fail(MOE_ERR_INVALID_ARG, "K must be in [1, %d] (got %d)", kMaxSlots, K);
     size_t eb = 0;
     moe_expert_bytes(cfg, &eb);
     if (expert_bytes != eb)
@@ -356,6 +406,7 @@ int moe_stream_ctx_create(const moe_cfg* cfg, const void* host_experts, size_t e
     ctx->expert_bytes = eb;
     ctx->dev_slots = static_cast<char*>(dev_slots);
     ctx->K = K;
+    for (int i = 0; i < kMaxSlots; ++i) ctx->slot_expert[i] = -1;
     hipError_t e = hipGetDevice(&ctx->device);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->copy_stream, hipStreamNonBlocking);
     for (int i = 0; i < K && e == hipSuccess; ++i) {
@@ -404,10 +455,63 @@ int moe_stream_ctx_set_order(moe_stream_ctx* ctx, int32_t policy, double tokens_
     return MOE_OK;
 }
 
+int moe_plan_slots(const int32_t* order, int32_t n, int32_t K, int32_t* slot_expert, int64_t* slot_tick, int64_t* tick,
+                   int32_t* slot_of, int32_t* load) {
+    REQUIRE(order, "order"); REQUIRE(slot_expert, "slot_expert"); REQUIRE(slot_tick, "slot_tick"); REQUIRE(tick, "tick");
+    REQUIRE(slot_of, "slot_of"); REQUIRE(load, "load");
+    if (n < 0 || n > 256) return fail(MOE_ERR_INVALID_ARG, "n must be in [0, 256] (got %d)", n);
+    if (K < 1 || K > kMaxSlots) return fail(MOE_ERR_INVALID_ARG, "K must be in [1, %d] (got %d)", kMaxSlots, K);
+    return plan_slots(order, n, K, slot_expert, slot_tick, tick, slot_of, load);
+}
+
+int moe_stream_ctx_keep_experts(moe_stream_ctx* ctx, int32_t on) {
+    REQUIRE(ctx, "sctx");
+    ctx->keep = on != 0;
+    if (!ctx->keep)
+        for (int i = 0; i < kMaxSlots; ++i) ctx->slot_expert[i] = -1;     // nothing is trusted once keeping is off
+    return MOE_OK;
+}
+
+int moe_stream_ctx_prefetch(moe_stream_ctx* ctx, int32_t expert) {
+    REQUIRE(ctx, "sctx");
+    if (!ctx->keep) return fail(MOE_ERR_INVALID_ARG, "prefetching needs moe_stream_ctx_keep_experts(sctx, 1)");
+    if (expert < 0 || expert >= ctx->cfg.E) return fail(MOE_ERR_INVALID_ARG, "expert %d is out of range", expert);
+    int32_t slot = 0, load = 0;
+    if (ctx->K >= ctx->cfg.E) {                 // every expert has its own slot
+        slot = expert;
+        load = ctx->slot_expert[expert] == expert ? 0 : 1;
+        ctx->slot_expert[expert] = expert;
+        ctx->slot_tick[expert] = ++ctx->tick;
+    } else if (int rc = plan_slots(&expert, 1, ctx->K, ctx->slot_expert, ctx->slot_tick, &ctx->tick, &slot, &load)) {
+        return rc;
+    }
+    if (!load) return MOE_OK;
+    if (ctx->released_valid[slot]) MOE_HIP_CHECK(hipStreamWaitEvent(ctx->copy_stream, ctx->released[slot], 0));
+    MOE_HIP_CHECK(hipMemcpyAsync(ctx->dev_slots + static_cast<size_t>(slot) * ctx->expert_bytes,
+                                 ctx->host_experts + static_cast<size_t>(expert) * ctx->expert_bytes, ctx->expert_bytes,
+                                 hipMemcpyHostToDevice, ctx->copy_stream));
+    MOE_HIP_CHECK(hipEventRecord(ctx->loaded[slot], ctx->copy_stream));
+    return MOE_OK;
+}
+
+int moe_stream_slots_that_fit(const moe_cfg* cfg, size_t reserve_bytes, int32_t* K) {
+    if (int rc = check_cfg(cfg)) return rc;
+    REQUIRE(K, "K");
+    size_t free_b = 0, total_b = 0, eb = 0;
+    MOE_HIP_CHECK(hipMemGetInfo(&free_b, &total_b));
+    moe_expert_bytes(cfg, &eb);
+    const size_t usable = free_b > reserve_bytes ? free_b - reserve_bytes : 0;
+    size_t k = usable / align256(eb);
+    if (k > static_cast<size_t>(kMaxSlots)) k = kMaxSlots;
+    if (k > static_cast<size_t>(cfg->E)) k = cfg->E;          // more slots than experts are never used
+    *K = static_cast<int32_t>(k);
+    return MOE_OK;
+}
+
 int moe_stream_ctx_last_order(const moe_stream_ctx* ctx, int32_t* order, int32_t* n_order, int32_t* satisfiable) {
     REQUIRE(ctx, "ctx"); REQUIRE(order, "order"); REQUIRE(n_order, "n_order");
-    for (int i = 0; i < ctx->n_loaded; ++i) order[i] = ctx->order[i];
-    *n_order = ctx->n_loaded;
+    for (int i = 0; i < ctx->n_order; ++i) order[i] = ctx->order[i];
+    *n_order = ctx->n_order;
     if (satisfiable != nullptr) *satisfiable = ctx->policy == MOE_ORDER_GREEDY ? ctx->satisfiable : 0;
     return MOE_OK;
 }
@@ -415,7 +519,7 @@ int moe_stream_ctx_last_order(const moe_stream_ctx* ctx, int32_t* order, int32_t
 int moe_stream_ctx_destroy(moe_stream_ctx* ctx) {
     if (ctx == nullptr) return MOE_OK;
     if (ctx->copy_stream) { (void)hipStreamSynchronize(ctx->copy_stream); (void)hipStreamDestroy(ctx->copy_stream); }
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < kMaxSlots; ++i) {
         if (ctx->loaded[i]) (void)hipEventDestroy(ctx->loaded[i]);
         if (ctx->released[i]) (void)hipEventDestroy(ctx->released[i]);
     }

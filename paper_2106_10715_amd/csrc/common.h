@@ -80,6 +80,9 @@ size_t ffn_plan_bytes(const moe_cfg& c);
 // Greedy execution order of the non-empty experts (host arrays); see schedule.hip.
 int schedule_order(const int32_t* counts, int E, double tokens_per_load, int K, int32_t* order, int* n_order,
                    int* satisfiable);
+// Slot and load decision for every expert of a call when slots keep their experts; see schedule.hip.
+int plan_slots(const int32_t* order, int n, int K, int32_t* slot_expert, int64_t* slot_tick, int64_t* tick,
+               int32_t* slot_of, int32_t* load);
 int launch_combine(const moe_cfg& c, const void* Yp, const int32_t* inv, const float* w, void* y, hipStream_t s);
 
 }  // namespace moe

@@ -51,4 +51,50 @@ int schedule_order(const int32_t* counts, int E, double r, int K, int32_t* order
     return MOE_OK;
 }
 
+// Which slot every expert of a call runs from when the K slots keep their experts between calls
+// (Section 6.2: K experts reside in GPU memory), and whether it has to be loaded first.  The whole
+// order of the call is known before its first load, so the resident expert whose next use in this
+// call lies furthest ahead gives way: an empty slot first, else never-used-again before used-later,
+// among equals the slot unused for longest, then the lowest slot.  For a known sequence this
+// minimises the number of loads.
+//   order[n]      experts in execution order
+//   slot_expert[K], slot_tick[K]  in/out: expert held by each slot (-1 = none) and when it was last used
+//   *tick         in/out: use counter
+//   slot_of[n], load[n]  out
+int plan_slots(const int32_t* order, int n, int K, int32_t* slot_expert, int64_t* slot_tick, int64_t* tick,
+               int32_t* slot_of, int32_t* load) {
+    for (int pos = 0; pos < n; ++pos) {
+        const int e = order[pos];
+        int s = -1;
+        for (int i = 0; i < K; ++i)
+            if (slot_expert[i] == e) { s = i; break; }
+        load[pos] = s < 0 ? 1 : 0;
+        if (s < 0) {
+            long best_next = -1;
+            for (int i = 0; i < K; ++i) {
+                long next = 0;                              // empty: better than any held expert
+                if (slot_expert[i] >= 0) {
+                    next = n + 1;                           // never again in this call
+                    for (int j = pos + 1; j < n; ++j)
+                        if (order[j] == slot_expert[i]) { next = j; break; }
+                }
+                const bool empty = slot_expert[i] < 0;
+                bool better;
+                if (s < 0) better = true;
+                else {
+                    const bool s_empty = slot_expert[s] < 0;
+                    if (empty != s_empty) better = empty;
+                    else if (next != best_next) better = next > best_next;
+                    else better = slot_tick[i] < slot_tick[s];      // equal ticks: the lower slot stays chosen
+                }
+                if (better) { s = i; best_next = next; }
+            }
+            slot_expert[s] = e;
+        }
+        slot_tick[s] = ++*tick;
+        slot_of[pos] = s;
+    }
+    return MOE_OK;
+}
+
 }  // namespace moe

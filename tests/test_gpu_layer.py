@@ -165,3 +165,73 @@ def test_streamed_greedy_order_is_the_oracles_and_changes_nothing(K, slots_n):
     torch.cuda.synchronize()
     assert torch.equal(L.y, y_res) and ctx.last_order() == (live, False)
     ctx.close()
+
+
+def test_kept_experts_are_not_loaded_again_and_change_nothing():
+    """Section 6.2's K resident experts across calls: with keeping on, a call copies only what no slot holds
+    (the oracle's replacement plan says which), and the output stays bitwise the resident one."""
+    from oracle import schedule_oracle as S
+    wl = W.Workload("keep", T=400, d=256, f=384, E=8, k=2, dtype="bf16", seed=91, zipf_s=1.0, n_dead=1)
+    L = H.build_layer(wl, host_copy=True)
+    M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)
+    torch.cuda.synchronize()
+    y_res = L.y.clone()
+    _, r, p, _ = oracle_layer(wl)
+    live = [e for e, c in enumerate(p.counts) if c > 0]
+    eb = M.moe_expert_bytes(L.cfg)
+    for K in (3, 8):
+        slots = torch.empty((K, eb), dtype=torch.uint8, device="cuda")
+        ctx = M.StreamCtx(L.cfg, L.host_packed, slots, K)
+        ctx.keep_experts(True)
+        held, used, tick = [-1] * K, [0] * K, 0
+        for rep in range(3):
+            L.y.fill_(float("nan"))
+            M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, None, ctx, L.y, L.ws)
+            torch.cuda.synchronize()
+            assert torch.equal(L.y, y_res), f"K={K} rep {rep}"
+            _, loads, held, used, tick = S.plan_slots(live, held, used, tick)
+            assert ctx.stats()["n_loaded"] == sum(loads)
+            assert ctx.last_order()[0] == live
+        if K >= len(live):
+            assert ctx.stats()["n_loaded"] == 0                  # everything stayed resident
+        else:
+            assert 0 < ctx.stats()["n_loaded"] <= len(live)
+        # greedy order on top of kept slots
+        ctx.set_order(M.ORDER_GREEDY, 64.0, 2)
+        M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, None, ctx, L.y, L.ws)
+        torch.cuda.synchronize()
+        assert torch.equal(L.y, y_res)
+        # keeping off: every expert is loaded again
+        ctx.keep_experts(False)
+        ctx.set_order(M.ORDER_ASCENDING)
+        M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, None, ctx, L.y, L.ws)
+        torch.cuda.synchronize()
+        assert torch.equal(L.y, y_res) and ctx.stats()["n_loaded"] == len(live)
+        ctx.close()
+
+
+def test_prefetched_expert_is_resident_when_the_layer_runs():
+    wl = W.Workload("prefetch", T=300, d=256, f=384, E=6, k=1, dtype="bf16", seed=92)
+    L = H.build_layer(wl, host_copy=True)
+    M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)
+    torch.cuda.synchronize()
+    y_res = L.y.clone()
+    eb = M.moe_expert_bytes(L.cfg)
+    slots = torch.empty((6, eb), dtype=torch.uint8, device="cuda")
+    ctx = M.StreamCtx(L.cfg, L.host_packed, slots, 6)
+    with pytest.raises(M.MoeError):
+        ctx.prefetch(0)                                          # needs keeping
+    ctx.keep_experts(True)
+    with pytest.raises(M.MoeError):
+        ctx.prefetch(6)
+    ctx.prefetch(0)
+    ctx.prefetch(4)
+    ctx.prefetch(0)                                              # already there: no second copy
+    L.y.fill_(float("nan"))
+    M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, None, ctx, L.y, L.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(L.y, y_res)
+    assert ctx.stats()["n_loaded"] == 4                          # all six experts hold tokens, two were prefetched
+    K = M.moe_stream_slots_that_fit(L.cfg, reserve_bytes=1 << 30)
+    assert K == wl.E                                             # tiny experts: capped by the expert count
+    ctx.close()

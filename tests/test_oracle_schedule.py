@@ -168,3 +168,67 @@ def test_library_order_edge_cases():
     for bad in (dict(counts=[1, -1], r=1.0, K=1), dict(counts=[1], r=0.0, K=1), dict(counts=[1], r=1.0, K=-1)):
         with pytest.raises(M.MoeError):
             M.moe_schedule_order(bad["counts"], bad["r"], bad["K"])
+
+
+# ---------------------------------------------------------------- experts that stay resident
+
+def _fewest_loads(order, held):
+    """Brute force over every possible choice of the slot to overwrite."""
+    from functools import lru_cache
+
+    @lru_cache(None)
+    def go(pos, state):
+        if pos == len(order):
+            return 0
+        if order[pos] in state:
+            return go(pos + 1, state)
+        return 1 + min(go(pos + 1, state[:i] + (order[pos],) + state[i + 1:]) for i in range(len(state)))
+    return go(0, tuple(held))
+
+
+def _random_slot_case(rng):
+    K, n, E = rng.randint(1, 5), rng.randint(0, 8), rng.randint(1, 7)
+    order = [rng.randrange(E) for _ in range(n)]
+    if rng.random() < 0.7:                                   # the library's use: every expert at most once
+        order = list(dict.fromkeys(order))
+    held = rng.sample(range(E), min(K, E)) + [-1] * max(0, K - E)
+    held = [h if rng.random() < 0.7 else -1 for h in held]
+    ticks = [rng.randint(0, 6) for _ in range(K)]
+    return order, held, ticks
+
+
+def test_slot_plan_hand_worked():
+    # two slots holding experts 3 and 5; the call runs 5, 7, 3: 5 is resident; 7 needs a slot: expert 3 is used
+    # again (position 2), expert 5 is not, so 5 gives way; 3 is still resident
+    slots, loads, held, used, tick = S.plan_slots([5, 7, 3], [3, 5], [10, 4], 20)
+    assert (slots, loads, held, tick) == ([1, 1, 0], [False, True, False], [3, 7], 23) and used == [23, 22]
+    # nothing resident, three experts, two slots: empty slots first, then the one unused for longest
+    assert S.plan_slots([1, 2, 4], [-1, -1], [0, 0], 0)[:3] == ([0, 1, 0], [True, True, True], [4, 2])
+    # as many slots as experts: the second call loads nothing
+    _, loads, held, used, tick = S.plan_slots([2, 0, 1], [-1, -1, -1], [0, 0, 0], 0)
+    assert loads == [True] * 3
+    assert S.plan_slots([1, 2, 0], held, used, tick)[1] == [False] * 3
+
+
+def test_slot_plan_needs_the_fewest_loads_possible():
+    rng = random.Random(23)
+    for _ in range(2500):
+        order, held, ticks = _random_slot_case(rng)
+        slots, loads, after, _, _ = S.plan_slots(order, held, ticks, 7)
+        assert sum(loads) == _fewest_loads(tuple(order), held)
+        state = list(held)                                   # and the plan is consistent with itself
+        for e, s, ld in zip(order, slots, loads):
+            assert ld == (e not in state)
+            if ld:
+                state[s] = e
+            assert state[s] == e
+        assert state == after
+
+
+def test_library_slot_plan_equals_oracle():
+    rng = random.Random(29)
+    for _ in range(1500):
+        order, held, ticks = _random_slot_case(rng)
+        want = S.plan_slots(order, held, ticks, 11)
+        got = M.moe_plan_slots(order, held, ticks, 11)
+        assert got[0] == want[0] and got[1] == want[1] and got[2] == want[2] and got[3] == want[3] and got[4] == want[4]
