@@ -117,7 +117,7 @@ def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures one GPU: the layer is built and measured on a single MI355X (--gpus 1); "
-              "multi-GPU sharding is described in DESIGN.md but not implemented", file=sys.stderr)
+              "sharding over several GPUs is described in the design notes, not built", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
