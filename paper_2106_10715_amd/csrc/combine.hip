@@ -19,13 +19,13 @@ __device__ inline uint32_t pack_bf16(float lo, float hi) {
 template <bool BF16>
 __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ Yp, const int32_t* __restrict__ inv,
                                                       const float* __restrict__ w, uint4* __restrict__ y, int k,
-                                                      int vec_per_row) {
+                                                      int vec_per_row, int n_rows) {
     const int t = blockIdx.x;
     int rows[kMaxK];
     float wt[kMaxK];
 #pragma unroll
     for (int j = 0; j < kMaxK; ++j) {
-        rows[j] = j < k ? inv[static_cast<size_t>(t) * k + j] : 0;
+        rows[j] = j < k ? min(max(inv[static_cast<size_t>(t) * k + j], 0), n_rows - 1) : 0;   // never outside Yp
         wt[j] = j < k ? w[static_cast<size_t>(t) * k + j] : 0.f;
     }
     for (int v = threadIdx.x; v < vec_per_row; v += 256) {
@@ -66,10 +66,10 @@ int launch_combine(const moe_cfg& c, const void* Yp, const int32_t* inv, const f
     const int vec_per_row = static_cast<int>(c.d * elem_size(c) / 16);
     if (c.dtype == MOE_BF16)
         hipLaunchKernelGGL(combine_kernel<true>, dim3(c.T), dim3(256), 0, s, static_cast<const uint4*>(Yp), inv, w,
-                           static_cast<uint4*>(y), c.k, vec_per_row);
+                           static_cast<uint4*>(y), c.k, vec_per_row, c.T * c.k);
     else
         hipLaunchKernelGGL(combine_kernel<false>, dim3(c.T), dim3(256), 0, s, static_cast<const uint4*>(Yp), inv, w,
-                           static_cast<uint4*>(y), c.k, vec_per_row);
+                           static_cast<uint4*>(y), c.k, vec_per_row, c.T * c.k);
     MOE_LAUNCH_CHECK("combine_kernel");
     return MOE_OK;
 }

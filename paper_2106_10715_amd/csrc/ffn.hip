@@ -46,7 +46,10 @@ __device__ inline float act_fn_bf16(float z, int act) {
 // [e_first, e_first + e_count) in order, at most tile_m rows per tile.  Returns false when the slot is past
 // the last tile (uniform for the block).  Must be called by all threads of the block.
 __device__ inline bool find_tile(const int32_t* __restrict__ offsets, int e_first, int e_count, int tile_m, int slot,
-                                 int& e_out, int& row_begin, int& rows) {
+                                 int total_rows, int& e_out, int& row_begin, int& rows) {
+    // segment of expert e, clamped so that whatever the offsets hold no tile reaches outside the rows there are
+    auto seg_lo = [&](int e) { return min(max(offsets[e], 0), total_rows); };
+    auto seg_hi = [&](int e) { return min(max(offsets[e + 1], seg_lo(e)), total_rows); };
     __shared__ int sh_e, sh_mt;
     if (threadIdx.x < 64) {
         const int lane = threadIdx.x;
@@ -54,7 +57,7 @@ __device__ inline bool find_tile(const int32_t* __restrict__ offsets, int e_firs
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int e = lane * 4 + q;
-            const int cnt = e < e_count ? offsets[e_first + e + 1] - offsets[e_first + e] : 0;
+            const int cnt = e < e_count ? seg_hi(e_first + e) - seg_lo(e_first + e) : 0;
             tl[q] = (cnt + tile_m - 1) / tile_m;
             sum += tl[q];
         }
@@ -81,11 +84,11 @@ __device__ inline bool find_tile(const int32_t* __restrict__ offsets, int e_firs
     e_out = e_first + sh_e;
     // the expert's rows are split evenly over its tiles (in multiples of 32 rows), not into full tiles
     // and a small remainder: equal tiles finish together and none is nearly empty
-    const int n = offsets[e_out + 1] - offsets[e_out];
+    const int lo = seg_lo(e_out), hi = seg_hi(e_out), n = hi - lo;
     const int tiles = (n + tile_m - 1) / tile_m;
     const int per_tile = min(tile_m, ((n + tiles - 1) / tiles + 31) & ~31);
-    row_begin = offsets[e_out] + sh_mt * per_tile;
-    rows = min(per_tile, offsets[e_out + 1] - row_begin);
+    row_begin = lo + sh_mt * per_tile;
+    rows = min(per_tile, hi - row_begin);
     return true;
 }
 
@@ -491,13 +494,14 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
 constexpr int kPlanHeader = 32;
 
 __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict__ offsets, int e_first, int e_count,
-                                                       int tile_m, int32_t* __restrict__ plan) {
+                                                       int tile_m, int32_t* __restrict__ plan, int total_rows, int max_tiles) {
     __shared__ int n[256], first[256], order[256], tl[256];
     const int t = threadIdx.x;
     int cnt = 0, lo = 0;
     if (t < e_count) {
-        lo = offsets[e_first + t];
-        cnt = offsets[e_first + t + 1] - lo;
+        // whatever the offsets hold, no tile may reach outside the total_rows rows or the work list
+        lo = min(max(offsets[e_first + t], 0), total_rows);
+        cnt = min(max(offsets[e_first + t + 1] - lo, 0), total_rows - lo);
     }
     n[t] = cnt;
     first[t] = lo;
@@ -520,10 +524,10 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
     if (my_tiles > 0) {
         const int per_tile = min(tile_m, ((my_n + my_tiles - 1) / my_tiles + 31) & ~31);
         int4* tiles = reinterpret_cast<int4*>(plan + kPlanHeader);
-        for (int mt = 0; mt < my_tiles; ++mt)
+        for (int mt = 0; mt < my_tiles && start + mt < max_tiles; ++mt)
             tiles[start + mt] = make_int4(e_first + mine, first[mine] + mt * per_tile, min(per_tile, my_n - mt * per_tile), 0);
     }
-    if (t == 255) plan[16] = start + my_tiles;
+    if (t == 255) plan[16] = min(start + my_tiles, max_tiles);
     if (t < 16) plan[t] = 0;
 }
 
@@ -630,12 +634,12 @@ template <bool GATED>
 __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ A, const int32_t* __restrict__ offsets,
                                                       int e_first, int e_count, const float* __restrict__ W,
                                                       size_t expert_stride_elems, size_t off_b0, size_t off_b1,
-                                                      float* __restrict__ C, int K, int N, int act) {
+                                                      float* __restrict__ C, int K, int N, int act, int total_rows) {
     __shared__ float As[16][kF32Tile + 4];
     __shared__ float B0s[16][kF32Tile + 4];
     __shared__ float B1s[GATED ? 16 : 1][kF32Tile + 4];
     int e, row_begin, rows;
-    if (!find_tile(offsets, e_first, e_count, kF32Tile, blockIdx.y, e, row_begin, rows)) return;
+    if (!find_tile(offsets, e_first, e_count, kF32Tile, blockIdx.y, total_rows, e, row_begin, rows)) return;
     const float* B0 = W + static_cast<size_t>(e - e_first) * expert_stride_elems + off_b0;
     const float* B1 = W + static_cast<size_t>(e - e_first) * expert_stride_elems + off_b1;
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
@@ -742,7 +746,8 @@ int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, 
             return n;
         }();
         auto grid_for = [&](long items) { return dim3(static_cast<unsigned>(items < n_cu ? items : n_cu)); };
-        hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, s, offsets, e_first, e_count, kTileM, plan);
+        hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, s, offsets, e_first, e_count, kTileM, plan,
+                           c.T * c.k, static_cast<int>(ffn_plan_tiles(c)));
         MOE_LAUNCH_CHECK("ffn_plan_kernel");
         if (before_up != nullptr) MOE_HIP_CHECK(hipEventRecord(before_up, s));
         const size_t down_off = 2 * df * 2;
@@ -777,12 +782,12 @@ int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, 
     const float* Wf = static_cast<const float*>(W);
     hipLaunchKernelGGL(ffn_f32_kernel<true>, dim3(c.f / kF32Tile, static_cast<unsigned>(slots)), dim3(256), 0, s,
                        static_cast<const float*>(Xp), offsets, e_first, e_count, Wf, stride, size_t(0), df,
-                       static_cast<float*>(H), c.d, c.f, c.act);
+                       static_cast<float*>(H), c.d, c.f, c.act, c.T * c.k);
     MOE_LAUNCH_CHECK("ffn_f32_kernel<up>");
     if (between != nullptr) MOE_HIP_CHECK(hipEventRecord(between, s));
     hipLaunchKernelGGL(ffn_f32_kernel<false>, dim3(c.d / kF32Tile, static_cast<unsigned>(slots)), dim3(256), 0, s,
                        static_cast<const float*>(H), offsets, e_first, e_count, Wf, stride, 2 * df, 2 * df,
-                       static_cast<float*>(Yp), c.f, c.d, c.act);
+                       static_cast<float*>(Yp), c.f, c.d, c.act, c.T * c.k);
     MOE_LAUNCH_CHECK("ffn_f32_kernel<down>");
     return MOE_OK;
 }
