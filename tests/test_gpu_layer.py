@@ -235,3 +235,33 @@ def test_prefetched_expert_is_resident_when_the_layer_runs():
     K = M.moe_stream_slots_that_fit(L.cfg, reserve_bytes=1 << 30)
     assert K == wl.E                                             # tiny experts: capped by the expert count
     ctx.close()
+
+
+def test_resident_layer_can_be_captured_in_a_graph_and_replayed():
+    """The resident layer is kernels only (its counters are cleared by a kernel, not by a memset), so it can
+    be recorded once and replayed; every replay, with other work in between, must equal the eager result."""
+    wl = W.Workload("graph", T=520, d=256, f=384, E=8, k=2, dtype="bf16", seed=93, zipf_s=1.0)
+    L = H.build_layer(wl)
+    M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)       # eager, also warms every lazy init
+    torch.cuda.synchronize()
+    y_eager = L.y.clone()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):                               # captures on a side stream that becomes the current one
+        M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)
+    torch.cuda.synchronize()
+    x0 = L.x.clone()
+    for rep in range(4):
+        L.y.fill_(float("nan"))
+        if rep == 2:                                        # new input in the same buffer: the graph must follow it
+            L.x.copy_(torch.roll(x0, 7, dims=0))
+        if rep == 3:
+            L.x.copy_(x0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        if rep == 2:
+            assert torch.equal(L.y, torch.roll(y_eager, 7, dims=0))          # the layer acts on tokens independently
+        else:
+            assert torch.equal(L.y, y_eager), f"replay {rep}"
+        scratch = torch.randn(1 << 16, device="cuda").sum().item()           # unrelated eager work between replays
+        assert scratch == scratch
