@@ -250,6 +250,19 @@ __device__ inline void mma_unit(f32x16 (&acc)[MBS][NF], const uint4 (&af)[Units<
     }
 }
 
+template <int LO, int HI, class F>
+__device__ inline void static_for(F&& f) {
+    if constexpr (LO < HI) {
+        f(std::integral_constant<int, LO>{});
+        static_for<LO + 1, HI>(f);
+    }
+}
+
+// The weight loads a step issues are spread over its MFMA units: a load holds the wave's issue slot for
+// some 16 cycles and the matrix pipe has only one instruction queued, so a run of loads lets it run dry.
+// Loads issued after the units 0..u of a step that issues n loads over U units, evenly:
+constexpr int loads_upto(int u, int n, int U) { return u < 0 ? 0 : ((u + 1) * n + U - 1) / U < n ? ((u + 1) * n + U - 1) / U : n; }
+
 // One pipeline step.  Entering, af[0] holds the fragments of unit 0 of this step; leaving, those of
 // unit 0 of the next step.
 //   cur, nxt : LDS buffers of this and of the next step
@@ -260,9 +273,12 @@ __device__ inline void mma_unit(f32x16 (&acc)[MBS][NF], const uint4 (&af)[Units<
 // The barrier sits before the MFMAs of the last unit: by then every fragment of this step has been
 // requested from cur and nxt is written, so the first fragments of the next step are fetched under
 // the last MFMAs instead of after them.
-template <int STAGE_AFTER, int N_YOUNGER, int NF, int MBS>
+//   issue_a  : issue_a(integral_constant mb) issues the activation load of row block mb this step prefetches
+//   issue_b  : issue_b(integral_constant i) issues load i of the kKS * NF weight loads this step prefetches
+template <int STAGE_AFTER, int N_YOUNGER, int NF, int MBS, class IssueA, class IssueB>
 __device__ inline void run_step(f32x16 (&acc)[MBS][NF], uint4 (&af)[2][Units<MBS>::G], const uint4* cur, uint4* nxt,
-                                const BFrags<NF>& b, ARegs<MBS>& a_next, BFrags<NF>& b_next, int lane, unsigned tid) {
+                                const BFrags<NF>& b, ARegs<MBS>& a_next, BFrags<NF>& b_next, int lane, unsigned tid,
+                                IssueA issue_a, IssueB issue_b) {
     constexpr int U = Units<MBS>::U;
     static_assert(STAGE_AFTER < U - 1, "staging must precede the barrier");
 #define FFN_UNIT(UU)                                                                                   \
@@ -273,6 +289,8 @@ __device__ inline void run_step(f32x16 (&acc)[MBS][NF], uint4 (&af)[2][Units<MBS
             read_unit<MBS, 0>(af[0], nxt, lane);                                                       \
         }                                                                                              \
         mma_unit<NF, MBS, (UU)>(acc, af[(UU) & 1], b);                                                 \
+        if constexpr ((UU) < MBS) issue_a(std::integral_constant<int, (UU)>{});                        \
+        static_for<loads_upto((UU) - 1, kKS * NF, U), loads_upto((UU), kKS * NF, U)>(issue_b);         \
         if constexpr ((UU) == STAGE_AFTER) {                                                           \
             wait_loads<N_YOUNGER>(a_next, b_next);                                                     \
             store_a(a_next, nxt, tid);                                                                    \
@@ -344,18 +362,21 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
 #pragma unroll
             for (int v = 0; v < 16; ++v) asm volatile("v_accvgpr_write_b32 %0, 0" : "=a"(acc[mb][j][v]));
 
-    // Pipeline depth.  Issue order inside a step is activations, then weights, so the loads younger
-    // than the ones awaited are known at compile time.
-    //   up to 6 row blocks: activations 2 steps ahead, ring of 4 weight steps.  Step c issues A(c+2),
-    //     B(c+3); half-way through it waits for A(c+1) (younger: B(c+2), A(c+2), B(c+3)), which also
-    //     covers the older B(c+1), and stages A(c+1).
-    //   7 or 8 row blocks (no registers for more): activations 1 step ahead, ring of 3.  Step c issues
-    //     A(c+1), B(c+2); just before its barrier it waits for A(c+1) (younger: B(c+2)) and stages it.
-    constexpr int AD = MBS <= 6 ? 2 : 1;
+    // Pipeline depth: activations 2 steps ahead (two register sets), weights 3 steps ahead (ring of 4).
+    // Step c issues A(c+2) and B(c+3), spread over its MFMA units: after unit u the activation load of row
+    // block u (if there is one) and the weight loads of that unit's share.  After unit kStageAfter it waits
+    // for A(c+1), whose last load was issued in step c-1 after unit MBS-1, stages it, and the barrier
+    // follows one unit later.  Loads return in order, so the wait only has to name how many younger loads
+    // may still be outstanding: the weight loads step c-1 issued from unit MBS-1 on, and what step c has
+    // issued so far.  Everything older, B(c+1) included, has then landed.
+    constexpr int AD = 2;
     constexpr int R = AD + 2;                   // weight ring; register indices repeat with period R
     constexpr int kB = kKS * NF;                // loads of one weight step
-    constexpr int kStageAfter = AD == 2 ? Units<MBS>::U / 2 - 1 : Units<MBS>::U - 2;
-    constexpr int kYounger = AD == 2 ? 2 * kB + MBS : kB;
+    constexpr int kU = Units<MBS>::U;
+    static_assert(MBS <= kU, "one activation load per unit");
+    constexpr int kStageAfter = kU - 2;
+    constexpr int kYounger = (kB - loads_upto(MBS - 2, kB, kU)) + (MBS < kStageAfter + 1 ? MBS : kStageAfter + 1) +
+                             loads_upto(kStageAfter, kB, kU);
     ARegs<MBS> areg[AD];
     BFrags<NF> ring[R];
     uint4 af[2][Units<MBS>::G];
@@ -370,6 +391,7 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
     auto fetch_b = [&](BFrags<NF>& dst, int chunk) {
         load_b(dst, static_cast<uint32_t>(chunk) * (kKS * 2048) + lane * 16, wave_base);
     };
+    const uint32_t lane_off = lane * 16;
     // Blocks that share a weight stream or an activation tile start their sweep over the reduction
     // dimension at the same step (and wrap around), other blocks at other steps, so that concurrent
     // waves do not all walk their weight streams, which lie a power of two apart, in lockstep.  The
@@ -380,7 +402,9 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
     int c = 0;
     if (chunks >= R) {
         asm volatile("; pipeline begin");       // from here to the matching end the build allows no spill code
-        // Prologue.  AD = 2: A(0) B(0) B(1) A(1) B(2);  AD = 1: A(0) B(0) B(1).  Then wait for A(0), B(0).
+        // Prologue: A(0) B(0) B(1) A(1) B(2), each as a block; then wait for A(0), B(0).  The first steps find
+        // more loads younger than the ones they wait for than the steady state assumes, which only makes
+        // their waits stricter.
         fetch_a(areg[0], at(0));
         fetch_b(ring[0], at(0));
         fetch_b(ring[1], at(1));
@@ -396,14 +420,27 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
 #define FFN_STEP(I)                                                                                        \
     {                                                                                                      \
         const int ci = c + (I);                                                                            \
-        fetch_a(areg[((I) + AD) % AD], at(min(ci + AD, last)));                                            \
-        fetch_b(ring[((I) + AD + 1) % R], at(min(ci + AD + 1, last)));                                     \
+        const char* a_base = reinterpret_cast<const char*>(A) +                                            \
+                             static_cast<size_t>(at(min(ci + AD, last))) * (kKC * 2);                      \
+        auto issue_a = [&](auto ic) {                                                                      \
+            constexpr int mb = decltype(ic)::value;                                                        \
+            if constexpr (mb + 1 < MBS)                                                                    \
+                ld_pinned<0>(areg[((I) + AD) % AD].v[mb], a_first, a_base + static_cast<size_t>(mb) * a_stride); \
+            else                                                                                           \
+                ld_pinned<0>(areg[((I) + AD) % AD].v[mb], a_last, a_base);                                 \
+        };                                                                                                 \
+        const uint32_t voff = static_cast<uint32_t>(at(min(ci + AD + 1, last))) * (kKS * 2048) + lane_off; \
+        auto issue_b = [&](auto ic) {                                                                      \
+            constexpr int i = decltype(ic)::value, ks = i / NF, j = i % NF;                                \
+            ld_pinned_stream<(ks & 1) * 2048 + j * 1024>(ring[((I) + AD + 1) % R].v[ks][j],                \
+                                                         voff + (ks >> 1) * 4096, wave_base);              \
+        };                                                                                                 \
         run_step<kStageAfter, kYounger>(acc, af, lds[ci & 1], lds[(ci + 1) & 1], ring[(I) % R],            \
-                                        areg[((I) + 1) % AD], ring[((I) + 1) % R], lane, tid);                  \
+                                        areg[((I) + 1) % AD], ring[((I) + 1) % R], lane, tid, issue_a,     \
+                                        issue_b);                                                          \
     }
         for (; c + R <= chunks; c += R) {
-            FFN_STEP(0) FFN_STEP(1) FFN_STEP(2)
-            if (R == 4) FFN_STEP(3)
+            FFN_STEP(0) FFN_STEP(1) FFN_STEP(2) FFN_STEP(3)
         }
 #undef FFN_STEP
         asm volatile("; pipeline end");
