@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -60,6 +61,77 @@ def check_no_spill(asm: str, kernel_pattern: str, what: str = "assembly") -> Non
             raise RuntimeError(f"{what}: spill code inside a hand-counted load pipeline of {kernel} (line {n}: {text})")
 
 
+
+_VREG = re.compile(r"\bv\[(\d+):(\d+)\]|\bv(\d+)\b")
+
+
+def _vregs(text: str) -> set:
+    out = set()
+    for lo, hi, one in _VREG.findall(text):
+        out |= set(range(int(lo), int(hi) + 1)) if lo else {int(one)}
+    return out
+
+
+def check_loads_in_flight(asm: str, kernel_pattern: str, what: str = "assembly") -> int:
+    """The pipelined loops of the named kernels keep loads in flight that the compiler does not know about
+    (it sees inline assembly that defines registers).  Whatever it schedules or copies there, no instruction
+    may touch a register whose load has not been waited for.  This walks every inner loop that lies between
+    "; pipeline begin" and "; pipeline end", twice around (the second round meets the loads the first left in
+    flight), keeping the loads in issue order: "s_waitcnt vmcnt(N)" retires all but the youngest N (loads
+    return in order), and any other use of a register with a load still pending is an error.  The loops must
+    be single blocks.  Returns the number of loops checked."""
+    lines = asm.splitlines()
+    kernel, inside, checked, n = None, False, 0, 0
+    while n < len(lines):
+        line = lines[n]
+        text = line.strip()
+        if line.startswith("_Z") and ":" in line:
+            name = line.split(":")[0]
+            kernel = name if kernel_pattern in name else None
+            inside = False
+        elif text.startswith(".end_amdhsa_kernel"):
+            kernel = None
+        if kernel is not None:
+            if "; pipeline begin" in text:
+                inside = True
+            elif "; pipeline end" in text:
+                inside = False
+            elif inside and line.startswith(".LBB") and "Depth=2" in (line + (lines[n + 1] if n + 1 < len(lines) else "")):
+                label = line.split(":")[0]
+                body, m = [], n + 1
+                while m < len(lines):
+                    t = lines[m].strip()
+                    if lines[m].startswith(".LBB") or "; pipeline" in t:
+                        raise RuntimeError(f"{what}: the pipelined loop {label} of {kernel} is not a single block (line {m + 1})")
+                    if t and not t.startswith(";"):
+                        body.append((m + 1, t.split(";")[0].strip()))
+                    if t.startswith("s_cbranch") and t.split()[-1] == label:
+                        break
+                    m += 1
+                pending = []                                  # (registers, line) in issue order
+                for round_ in range(2):
+                    for ln, t in body:
+                        op = t.split()[0]
+                        if op == "s_waitcnt":
+                            got = re.search(r"vmcnt\((\d+)\)", t)
+                            if got:
+                                keep = int(got.group(1))
+                                pending = pending[len(pending) - keep:] if 0 < keep < len(pending) else ([] if keep == 0 else pending)
+                            continue
+                        used = _vregs(t)
+                        for regs, at in pending:
+                            if used & regs:
+                                raise RuntimeError(f"{what}: {kernel}: line {ln} ({t}) touches v{min(used & regs)}, whose load "
+                                                   f"(line {at}) has not been waited for")
+                        if op.startswith(("global_load", "buffer_load", "flat_load")):
+                            dst = _vregs(t.split(",")[0])
+                            pending.append((dst, ln))
+                checked += 1
+                n = m
+        n += 1
+    return checked
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(HERE, "_build", src.replace(".hip", ".o"))
     cmd = [_hipcc(), *FLAGS, *EXTRA.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
@@ -71,7 +143,10 @@ def _compile(src: str) -> str:
                              os.path.join(CSRC, src), "-o", asm], capture_output=True, text=True)
         if ra.returncode != 0:
             raise RuntimeError(f"hipcc -S failed on {src}:\n{ra.stderr}")
-        check_no_spill(open(asm).read(), NO_SPILL[src], src)
+        text = open(asm).read()
+        check_no_spill(text, NO_SPILL[src], src)
+        if check_loads_in_flight(text, NO_SPILL[src], src) == 0:
+            raise RuntimeError(f"{src}: no pipelined loop found to verify (markers missing?)")
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{err}")

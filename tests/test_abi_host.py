@@ -129,3 +129,34 @@ def test_build_refuses_spill_code_inside_a_load_pipeline():
     ])
     with pytest.raises(RuntimeError, match="spill code"):
         check_no_spill(nested, "ffn_mfma")
+
+
+def test_build_refuses_a_loop_that_touches_a_register_with_a_load_in_flight():
+    """The build's second assembly check walks the pipelined loops twice with the loads in issue order."""
+    from paper_2106_10715_amd.build import check_loads_in_flight
+
+    def kernel(body):
+        return "\n".join(["_ZN3moe8ffn_mfma_kernelEv: ; @x", "\t; pipeline begin",
+                          ".LBB0_2:                                ;   Parent Loop BB0_1 Depth=1",
+                          "                                        ; =>  This Inner Loop Header: Depth=2"]
+                         + ["\t" + l for l in body] + ["\ts_cbranch_scc1 .LBB0_2", "\t; pipeline end", "\t.end_amdhsa_kernel"])
+
+    good = ["global_load_dwordx4 v[8:11], v40, s[2:3] offset:0 nt",       # prefetch for the next round
+            "s_waitcnt vmcnt(1)",                                          # the previous round's load has landed
+            "v_mfma_f32_32x32x16_bf16 v[16:31], v[4:7], v[12:15], v[16:31]",
+            "global_load_dwordx4 v[12:15], v40, s[2:3] offset:1024 nt",    # refilled right after its last use
+            "s_waitcnt vmcnt(1)",
+            "v_mfma_f32_32x32x16_bf16 v[16:31], v[4:7], v[8:11], v[16:31]"]
+    assert check_loads_in_flight(kernel(good), "ffn_mfma") == 1
+    # the consumer moved above its wait
+    early = [good[0], good[2], good[1]] + good[3:]
+    with pytest.raises(RuntimeError, match="has not been waited for"):
+        check_loads_in_flight(kernel(early), "ffn_mfma")
+    # a copy of a register that was loaded in the previous round and is still in flight at the loop end
+    copied = good + ["v_mov_b64_e32 v[50:51], v[12:13]"]
+    with pytest.raises(RuntimeError, match="has not been waited for"):
+        check_loads_in_flight(kernel(copied), "ffn_mfma")
+    # other kernels are not looked at; a loop of several blocks cannot be verified and is refused
+    assert check_loads_in_flight(kernel(copied).replace("ffn_mfma", "other"), "ffn_mfma") == 0
+    with pytest.raises(RuntimeError, match="not a single block"):
+        check_loads_in_flight(kernel(good[:2] + [".LBB0_3:"] + good[2:]).replace("\t.LBB0_3:", ".LBB0_3:"), "ffn_mfma")
