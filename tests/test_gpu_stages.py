@@ -336,3 +336,33 @@ def test_combine_matches_oracle(T, d, k, dtype):
     ref = O.combine(Yp.astype(np.float64), inv, w)
     got = H.to_f64(y)
     assert rel_l2(got, ref) <= (1e-6 if dtype == "f32" else 4e-3)     # one rounding to storage
+
+
+def _random_ffn_case(seed):
+    rng = np.random.default_rng(seed)
+    d = int(rng.choice([64, 128, 192, 256, 448, 1024]))
+    f = int(rng.choice([64, 128, 320, 576, 1024]))
+    E = int(rng.integers(1, 9))
+    kind = seed % 3
+    if kind == 0:
+        counts = [int(c) for c in rng.integers(0, 70, size=E)]
+    elif kind == 1:
+        counts = [int(c) for c in rng.choice([0, 1, 31, 32, 33, 255, 256, 257, 300, 513], size=E)]
+    else:
+        counts = [int(800 / (i + 1) ** 1.3) for i in range(E)]
+    if sum(counts) == 0:
+        counts[0] = 5
+    return d, f, E, counts
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_expert_ffn_random_shapes(seed):
+    """Seeded sweep over widths, depths and segment lengths (empty, one row, around the 32-row block and the
+    256-row tile, several tiles, skewed): every segment on its own against the oracle."""
+    d, f, E, counts = _random_ffn_case(1000 + seed)
+    got, ref, offsets = run_ffn(sum(counts), d, f, E, 1, "bf16", counts, seed % 2, seed=seed)
+    assert np.isfinite(got).all()
+    for e in range(E):
+        lo, hi = offsets[e], offsets[e + 1]
+        if hi > lo:
+            assert rel_l2(got[lo:hi], ref[lo:hi]) <= TOL["bf16"], f"expert {e}: d={d} f={f} counts={counts}"
