@@ -30,16 +30,25 @@ __device__ inline float act_fn(float z, int act) {
     return 0.5f * z * (1.0f + tanhf(u));
 }
 
-// Activation for results that are rounded to bf16 right away: erf from the rational-times-Gaussian
-// approximation 7.1.26 of Abramowitz & Stegun (|error| <= 1.5e-7 on erf, 5e-7 on GELU, three orders
-// below the bf16 rounding of the result) instead of the library erff, which is several times longer.
+// Exact GELU for results that are rounded to bf16 right away, written on the lower tail of the normal
+// distribution: with q(a) = 0.5 erfc(a / sqrt 2), GELU(z) = z Phi(z) = max(z, 0) - |z| q(|z|), which has no
+// cancellation for negative z.  log2 q is smooth, so q = exp2(P(a)) with P a polynomial of degree 6,
+// fitted on [0, 8] with the error weighted by a q(a) (so that the absolute error of GELU is level):
+// |error| <= 1e-7 on GELU in fp32 arithmetic, four orders below the bf16 rounding of the result, in six
+// fused multiply-adds and one hardware exponential instead of the several times longer library erff.
+// Beyond 8, q < 1e-15 and the argument is clamped (by a comparison that lets a NaN through).
+constexpr float kGeluTail[7] = {-0.999993085861206f,   -1.1512017250061035f,   -0.4587709605693817f, -0.05341210961341858f,
+                                0.008080719038844109f, -0.0007692205253988504f, 3.309290696051903e-05f};
 __device__ inline float act_fn_bf16(float z, int act) {
     if (act != 0) return act_fn(z, act);
-    const float x = fabsf(z) * 0.70710678118654752f;
-    const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * x);
-    const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
-    const float erf_abs = 1.0f - poly * __expf(-x * x);
-    return 0.5f * z * (1.0f + copysignf(erf_abs, z));
+    const float a = fabsf(z);
+    const float ac = a > 8.0f ? 8.0f : a;
+    float p = kGeluTail[6];
+#pragma unroll
+    for (int i = 5; i >= 0; --i) p = fmaf(p, ac, kGeluTail[i]);
+    float relu;                                  // one instruction: fmaxf would first quiet a signalling NaN, and a NaN comes through ac anyway
+    asm("v_max_f32 %0, 0, %1" : "=v"(relu) : "v"(z));
+    return fmaf(-ac, __builtin_amdgcn_exp2f(p), relu);
 }
 
 // Which (expert, row tile) a block works on: tile slot `slot` counted over the experts
@@ -244,7 +253,7 @@ __device__ inline void mma_unit(f32x16 (&acc)[MBS][NF], const uint4 (&af)[Units<
         if (mb0 + i < MBS) {
 #pragma unroll
             for (int j = 0; j < NF; ++j)
-                acc[mb0 + i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af[i]), as_bf16x8(b.v[ks][j]),
+                acc[mb0 + i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(b.v[ks][j]), as_bf16x8(af[i]),
                                                                           acc[mb0 + i][j], 0, 0, 0);
         }
     }
@@ -258,46 +267,116 @@ __device__ inline void static_for(F&& f) {
     }
 }
 
-// The weight loads a step issues are spread over its MFMA units: a load holds the wave's issue slot for
-// some 16 cycles and the matrix pipe has only one instruction queued, so a run of loads lets it run dry.
-// Loads issued after the units 0..u of a step that issues n loads over U units, evenly:
+// Everything a pipeline step does besides its MFMAs is spread over them, one instruction after each
+// MFMA: a load or an LDS access holds the wave's issue slot for some 16 cycles and the matrix pipe
+// has only one instruction queued, so a run of them lets it run dry, and a wait that directly follows
+// the LDS writes of the whole tile stalls the wave for their full latency.
+// Loads (or LDS writes) done after the units 0..u of a step that spreads n of them evenly over U units:
 constexpr int loads_upto(int u, int n, int U) { return u < 0 ? 0 : ((u + 1) * n + U - 1) / U < n ? ((u + 1) * n + U - 1) / U : n; }
+// The staging writes (one per row block) go into the units before the last one, which holds the barrier.
+constexpr int writes_upto(int u, int n, int U) { return loads_upto(u, n, U - 1); }
+constexpr int unit_of_write(int w, int n, int U) {
+    int u = 0;
+    while (writes_upto(u, n, U) <= w) ++u;
+    return u;
+}
+// Global loads a step has issued before those of unit u: one activation load per unit while there are
+// row blocks left, then the unit's share of the nb weight loads.
+constexpr int issued_before(int u, int MBS, int nb, int U) { return (u < MBS ? u : MBS) + loads_upto(u - 1, nb, U); }
+// Loads younger than the activation load of row block w at the moment the next step stages that block:
+// what the issuing step issued after it, and what the staging step has issued before the unit that
+// stages it.  Loads return in order, so waiting until at most this many are outstanding means the block
+// (and every weight load older than it) has landed.
+constexpr int younger_at_write(int w, int MBS, int nb, int U) {
+    return (MBS + nb - issued_before(w, MBS, nb, U) - 1) + issued_before(unit_of_write(w, MBS, U), MBS, nb, U);
+}
+
+template <int MBS>
+constexpr int unit_rows(int u) {
+    const int left = MBS - (u % Units<MBS>::H) * Units<MBS>::G;
+    return left > Units<MBS>::G ? Units<MBS>::G : (left < 0 ? 0 : left);
+}
+// fragment I of unit UNIT, from the activation tile in lds_buf
+template <int MBS, int UNIT, int I>
+__device__ inline void read_frag(uint4 (&af)[Units<MBS>::G], const uint4* lds_buf, int lane) {
+    constexpr int ks = UNIT / Units<MBS>::H, mb = (UNIT % Units<MBS>::H) * Units<MBS>::G + I;
+    af[I] = lds_buf[(lane & 31) * kLdsRow + (lane >> 5) + 2 * ks + mb * 32 * kLdsRow];
+}
+// MFMA M of unit UNIT: row block M / NF of the unit, weight fragment M % NF
+template <int NF, int MBS, int UNIT, int M>
+__device__ inline void mma_one(f32x16 (&acc)[MBS][NF], const uint4 (&af)[Units<MBS>::G], const BFrags<NF>& b) {
+    constexpr int ks = UNIT / Units<MBS>::H, i = M / NF, j = M % NF, mb = (UNIT % Units<MBS>::H) * Units<MBS>::G + i;
+    acc[mb][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(b.v[ks][j]), as_bf16x8(af[i]), acc[mb][j], 0, 0, 0);
+}
+// Row block mb of the staged activations has landed once at most N_YOUNGER loads are outstanding; it goes
+// into the LDS tile (thread t holds the 16-byte piece t%8 of row mb*32 + t/8).
+template <int N_YOUNGER>
+__device__ inline void stage_block(u32x4& v, uint4* lds_buf, unsigned tid, int mb) {
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N_YOUNGER) : "memory");
+    asm volatile("" : "+v"(v));
+    reinterpret_cast<u32x4*>(lds_buf)[(tid >> 3) * kLdsRow + (tid & 7) + mb * 32 * kLdsRow] = v;
+}
 
 // One pipeline step.  Entering, af[0] holds the fragments of unit 0 of this step; leaving, those of
 // unit 0 of the next step.
 //   cur, nxt : LDS buffers of this and of the next step
 //   b        : weight fragments of this step
-//   a_next, b_next : registers of the next step's activations and weights (loads in flight); after the
-//              MFMAs of unit STAGE_AFTER at most N_YOUNGER younger loads may be outstanding, which
-//              means both have landed, and the activations are staged into nxt
-// The barrier sits before the MFMAs of the last unit: by then every fragment of this step has been
-// requested from cur and nxt is written, so the first fragments of the next step are fetched under
-// the last MFMAs instead of after them.
+//   a_next, b_next : registers of the next step's activations and weights (loads in flight)
 //   issue_a  : issue_a(integral_constant mb) issues the activation load of row block mb this step prefetches
 //   issue_b  : issue_b(integral_constant i) issues load i of the kKS * NF weight loads this step prefetches
-template <int STAGE_AFTER, int N_YOUNGER, int NF, int MBS, class IssueA, class IssueB>
+// After MFMA s of a unit comes its s-th other instruction, in this order: the LDS reads of the next
+// unit's fragments, the staging of the row blocks that fall to this unit (each behind its own wait), the
+// unit's activation load, its weight loads.  The last unit holds the barrier after its second MFMA: all
+// fragments of this step were requested a unit earlier and nxt was completed a unit earlier, so the wait
+// in front of the barrier finds nothing outstanding, and the first fragments of the next step are read
+// from nxt under the remaining MFMAs.  nxt may be written from the start of the step: its last readers
+// passed the barrier of the step before.
+template <int NF, int MBS, class IssueA, class IssueB>
 __device__ inline void run_step(f32x16 (&acc)[MBS][NF], uint4 (&af)[2][Units<MBS>::G], const uint4* cur, uint4* nxt,
                                 const BFrags<NF>& b, ARegs<MBS>& a_next, BFrags<NF>& b_next, int lane, unsigned tid,
                                 IssueA issue_a, IssueB issue_b) {
-    constexpr int U = Units<MBS>::U;
-    static_assert(STAGE_AFTER < U - 1, "staging must precede the barrier");
-#define FFN_UNIT(UU)                                                                                   \
-    if constexpr ((UU) < U) {                                                                          \
-        if constexpr ((UU) + 1 < U) read_unit<MBS, (UU) + 1>(af[((UU) + 1) & 1], cur, lane);           \
-        if constexpr ((UU) + 1 == U) {                                                                 \
-            __syncthreads();                                                                           \
-            read_unit<MBS, 0>(af[0], nxt, lane);                                                       \
-        }                                                                                              \
-        mma_unit<NF, MBS, (UU)>(acc, af[(UU) & 1], b);                                                 \
-        if constexpr ((UU) < MBS) issue_a(std::integral_constant<int, (UU)>{});                        \
-        static_for<loads_upto((UU) - 1, kKS * NF, U), loads_upto((UU), kKS * NF, U)>(issue_b);         \
-        if constexpr ((UU) == STAGE_AFTER) {                                                           \
-            wait_loads<N_YOUNGER>(a_next, b_next);                                                     \
-            store_a(a_next, nxt, tid);                                                                    \
-        }                                                                                              \
-    }
-    FFN_UNIT(0) FFN_UNIT(1) FFN_UNIT(2) FFN_UNIT(3) FFN_UNIT(4) FFN_UNIT(5) FFN_UNIT(6) FFN_UNIT(7)
-#undef FFN_UNIT
+    constexpr int U = Units<MBS>::U, kB = kKS * NF;
+    static_for<0, U>([&](auto uc) {
+        constexpr int UU = decltype(uc)::value;
+        constexpr bool kLast = UU + 1 == U;
+        constexpr int M = unit_rows<MBS>(UU) * NF;                 // MFMAs of this unit
+        constexpr int NU = kLast ? 0 : UU + 1;                     // the unit whose fragments are fetched meanwhile
+        constexpr int nR = unit_rows<MBS>(NU);
+        constexpr int w0 = kLast ? MBS : writes_upto(UU - 1, MBS, U), nW = (kLast ? MBS : writes_upto(UU, MBS, U)) - w0;
+        constexpr int nA = UU < MBS ? 1 : 0;
+        constexpr int b0 = loads_upto(UU - 1, kB, U), nB = loads_upto(UU, kB, U) - b0;
+        constexpr int nOther = nR + nW + nA + nB;
+        constexpr int kFirst = kLast && M > 1 ? 1 : 0;             // other instruction s follows MFMA kFirst + s
+        auto other = [&](auto sc) {
+            constexpr int s = decltype(sc)::value;
+            if constexpr (s < nR) {
+                read_frag<MBS, NU, s>(af[NU & 1], kLast ? nxt : cur, lane);
+            } else if constexpr (s < nR + nW) {
+                constexpr int w = w0 + s - nR;
+                stage_block<younger_at_write(w, MBS, kB, U)>(a_next.v[w], nxt, tid, w);
+                if constexpr (w == 0) {                            // the weights of the next step are older than its activations
+#pragma unroll
+                    for (int ks = 0; ks < kKS; ++ks)
+#pragma unroll
+                        for (int j = 0; j < NF; ++j) asm volatile("" : "+v"(b_next.v[ks][j]));
+                }
+            } else if constexpr (s < nR + nW + nA) {
+                issue_a(std::integral_constant<int, UU + 0 * s>{});     // (made dependent on s: only instantiated when taken)
+            } else {
+                issue_b(std::integral_constant<int, b0 + s - nR - nW - nA>{});
+            }
+        };
+        static_for<0, M>([&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            mma_one<NF, MBS, UU, m>(acc, af[UU & 1], b);
+            if constexpr (kLast && m == kFirst) __syncthreads();
+            if constexpr (m >= kFirst) {
+                constexpr int lo = m - kFirst;
+                constexpr int hi = m == M - 1 ? nOther : (lo + 1 < nOther ? lo + 1 : nOther);
+                static_for<lo, hi>(other);
+            }
+        });
+    });
 }
 
 // A step without any overlap, for the few steps that do not fill a group of the unrolled pipeline:
@@ -363,20 +442,16 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
             for (int v = 0; v < 16; ++v) asm volatile("v_accvgpr_write_b32 %0, 0" : "=a"(acc[mb][j][v]));
 
     // Pipeline depth: activations 2 steps ahead (two register sets), weights 3 steps ahead (ring of 4).
-    // Step c issues A(c+2) and B(c+3), spread over its MFMA units: after unit u the activation load of row
-    // block u (if there is one) and the weight loads of that unit's share.  After unit kStageAfter it waits
-    // for A(c+1), whose last load was issued in step c-1 after unit MBS-1, stages it, and the barrier
-    // follows one unit later.  Loads return in order, so the wait only has to name how many younger loads
-    // may still be outstanding: the weight loads step c-1 issued from unit MBS-1 on, and what step c has
-    // issued so far.  Everything older, B(c+1) included, has then landed.
+    // Step c issues A(c+2) and B(c+3), spread over its MFMA units (after unit u the activation load of row
+    // block u, if there is one, and the weight loads of that unit's share), and stages A(c+1), one row
+    // block at a time, in the units before its last: row block w was requested by step c-1 in unit w and
+    // is waited for about one step later, by the count of loads younger than it (younger_at_write).
+    // Everything older, B(c+1) included, has then landed.
     constexpr int AD = 2;
     constexpr int R = AD + 2;                   // weight ring; register indices repeat with period R
     constexpr int kB = kKS * NF;                // loads of one weight step
     constexpr int kU = Units<MBS>::U;
     static_assert(MBS <= kU, "one activation load per unit");
-    constexpr int kStageAfter = kU - 2;
-    constexpr int kYounger = (kB - loads_upto(MBS - 2, kB, kU)) + (MBS < kStageAfter + 1 ? MBS : kStageAfter + 1) +
-                             loads_upto(kStageAfter, kB, kU);
     ARegs<MBS> areg[AD];
     BFrags<NF> ring[R];
     uint4 af[2][Units<MBS>::G];
@@ -435,9 +510,8 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
             ld_pinned_stream<(ks & 1) * 2048 + j * 1024>(ring[((I) + AD + 1) % R].v[ks][j],                \
                                                          voff + (ks >> 1) * 4096, wave_base);              \
         };                                                                                                 \
-        run_step<kStageAfter, kYounger>(acc, af, lds[ci & 1], lds[(ci + 1) & 1], ring[(I) % R],            \
-                                        areg[((I) + 1) % AD], ring[((I) + 1) % R], lane, tid, issue_a,     \
-                                        issue_b);                                                          \
+        run_step(acc, af, lds[ci & 1], lds[(ci + 1) & 1], ring[(I) % R], areg[((I) + 1) % AD],             \
+                 ring[((I) + 1) % R], lane, tid, issue_a, issue_b);                                        \
     }
         for (; c + R <= chunks; c += R) {
             FFN_STEP(0) FFN_STEP(1) FFN_STEP(2) FFN_STEP(3)
@@ -468,19 +542,22 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
         for (int mb = 0; mb < MBS; ++mb) asm volatile("" : : "v"(areg[i].v[mb]));
     __syncthreads();                            // the last LDS reads are done before the epilogue reuses the LDS
     tid = thread_id(wave_s);                    // rebuilt: the first copy need not survive the main loop
-    // Epilogue through LDS (the activation buffers are free now): every wave applies the activation to
-    // its accumulators and writes bf16 values into a row-major tile of the block's columns; then the
-    // whole block stores that tile with 16 bytes per lane, whole 64-byte segments per row.  All rows
-    // are computed (clamped duplicates give finite values), only real rows are stored.
+    // Epilogue through LDS (the activation buffers are free now).  The weight fragment is the first MFMA
+    // operand and the activation fragment the second, so the accumulators hold the transposed tile: lane l
+    // has token row l%32 of its row block and, in v = 4g..4g+3, the four neighbouring output columns
+    // 8g + 4(l/32) + 0..3.  Every wave applies the activation, rounds four neighbours to bf16 and writes them
+    // as one 8-byte piece into a row-major tile of the block's columns; then the whole block stores that tile
+    // with 16 bytes per lane, whole 64-byte segments per row.  All rows are computed (clamped duplicates
+    // give finite values), only real rows are stored.
     constexpr int W = 32 * (GATED ? 1 : NF);            // output columns per wave
-    constexpr int kTileRowBytes = 4 * W * 2 + 16;       // padded: the two row groups of a wave hit different banks
+    constexpr int kTileRowBytes = 4 * W * 2 + 16;       // padded: 4 dwords mod 32, eight rows x two halves cover the banks once
     constexpr int kRowsPerPass = W == 32 ? 256 : 128;   // tile rows that fit the LDS
     constexpr int kLanesPerRow = W / 2;                 // 16-byte stores per tile row
     constexpr int kRowsPerIter = 256 / kLanesPerRow;
     char* tile = reinterpret_cast<char*>(&lds[0][0]);
     static_assert(kRowsPerPass * kTileRowBytes <= static_cast<int>(sizeof(lds)), "epilogue tile must fit the LDS buffers");
     const int wave = wave_s;
-    const int col_in = (tid & 31), row_in = 4 * ((tid & 63) >> 5);
+    const int row_in = (tid & 31), col_in = 4 * ((tid & 63) >> 5);
 #pragma unroll
     for (int p0 = 0; p0 < MBS * 32; p0 += kRowsPerPass) {
         if (p0 > 0) __syncthreads();                    // the previous pass has been stored
@@ -489,18 +566,23 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
         auto fill = [&](auto exact) {
 #pragma unroll
             for (int mb = p0 / 32; mb < MBS && mb < (p0 + kRowsPerPass) / 32; ++mb) {
+                char* trow = tile + (mb * 32 + row_in - p0) * kTileRowBytes + (wave * W + col_in) * 2;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    // accumulator layout of the 32x32 MFMA: lane holds column lane%32, rows 8*(v/4) + 4*(lane/32) + v%4
-                    const int r = mb * 32 + 8 * (v >> 2) + row_in + (v & 3) - p0;
-                    uint16_t* trow = reinterpret_cast<uint16_t*>(tile + r * kTileRowBytes) + wave * W + col_in;
-                    if constexpr (GATED) {
-                        const float h = act_fn_bf16(acc[mb][0][v], decltype(exact)::value ? 0 : 1) * acc[mb][NF - 1][v];
-                        trow[0] = __builtin_bit_cast(uint16_t, static_cast<__bf16>(h));
-                    } else {
+                for (int j = 0; j < (GATED ? 1 : NF); ++j) {
 #pragma unroll
-                        for (int j = 0; j < NF; ++j)
-                            trow[32 * j] = __builtin_bit_cast(uint16_t, static_cast<__bf16>(acc[mb][j][v]));
+                    for (int g = 0; g < 4; ++g) {
+                        float h[4];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            if constexpr (GATED)
+                                h[i] = act_fn_bf16(acc[mb][0][4 * g + i], decltype(exact)::value ? 0 : 1) * acc[mb][NF - 1][4 * g + i];
+                            else
+                                h[i] = acc[mb][j][4 * g + i];
+                        }
+                        typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+                        const bf16x4 packed = {static_cast<__bf16>(h[0]), static_cast<__bf16>(h[1]), static_cast<__bf16>(h[2]),
+                                               static_cast<__bf16>(h[3])};
+                        *reinterpret_cast<uint2*>(trow + (32 * j + 8 * g) * 2) = __builtin_bit_cast(uint2, packed);
                     }
                 }
             }

@@ -160,3 +160,30 @@ def test_build_refuses_a_loop_that_touches_a_register_with_a_load_in_flight():
     assert check_loads_in_flight(kernel(copied).replace("ffn_mfma", "other"), "ffn_mfma") == 0
     with pytest.raises(RuntimeError, match="not a single block"):
         check_loads_in_flight(kernel(good[:2] + [".LBB0_3:"] + good[2:]).replace("\t.LBB0_3:", ".LBB0_3:"), "ffn_mfma")
+
+
+def test_gelu_tail_polynomial_of_the_ffn_kernel_is_accurate():
+    """The bf16 FFN epilogue evaluates exact GELU as max(z, 0) - a 2^P(a), a = min(|z|, 8), with the seven
+    coefficients of P written in ffn.hip.  Evaluated here in float32 steps like the kernel's fused
+    multiply-adds, the result must agree with z Phi(z) from the error function to 1.5e-7 absolute over
+    the whole range, and 2^P(a) with the normal tail 0.5 erfc(a / sqrt 2) to 1e-3 relative up to a = 4 (the fit levels the
+    absolute error of GELU, so the relative error of the tail grows as the tail vanishes)."""
+    import numpy as np
+    from scipy.special import erfc
+    src = open(os.path.join(os.path.dirname(M.__file__), "csrc", "ffn.hip")).read()
+    body = re.search(r"kGeluTail\[7\]\s*=\s*\{([^}]*)\}", src).group(1)
+    coef = [np.float32(float(t.strip().rstrip("f"))) for t in body.split(",")]
+    assert len(coef) == 7
+    z = np.linspace(-12.0, 12.0, 1_200_001).astype(np.float32)
+    a = np.minimum(np.abs(z), np.float32(8.0))
+    p = np.full_like(a, coef[6])
+    for c in coef[5::-1]:
+        p = (p.astype(np.float64) * a.astype(np.float64) + np.float64(c)).astype(np.float32)   # one rounding, as an fma
+    q = np.exp2(p.astype(np.float64))
+    gelu = np.maximum(z, 0).astype(np.float64) - a.astype(np.float64) * q
+    z64 = z.astype(np.float64)
+    exact = z64 * 0.5 * erfc(-z64 / np.sqrt(2.0))
+    assert np.abs(gelu - exact).max() <= 1.5e-7
+    near = a <= 4.0
+    tail = 0.5 * erfc(a[near].astype(np.float64) / np.sqrt(2.0))
+    assert np.abs(q[near] / tail - 1.0).max() <= 1e-3
