@@ -32,6 +32,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4a", "c4b", "c5", "c6"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tokens", type=int, default=None,
+                    help="run the workload's layer on this many tokens instead of its own count (a sweep over batch sizes; "
+                         "the figure the workload is quoted on is the one without this option)")
     ap.add_argument("--streamed", action="store_true", help="run the workload with host-streamed experts even if it is defined resident")
     ap.add_argument("--slots", type=int, default=2, help="device slots of the streamed mode")
     ap.add_argument("--order", default="ascending", choices=["ascending", "greedy"],
@@ -133,6 +136,10 @@ def main():
     torch.cuda.set_device(0)
     M.lib()                                     # fails loudly if the HIP library is not built
     wl = W.CONFIGS[args.workload]
+    if args.tokens is not None:
+        if args.tokens < 1:
+            sys.exit("bench.py: --tokens must be positive")
+        wl = wl.with_tokens(args.tokens)
     if args.streamed and not wl.streamed:
         import dataclasses
         wl = dataclasses.replace(wl, streamed=True, name=wl.name + "-streamed")
@@ -231,7 +238,7 @@ def main():
         # the up kernel is bound by whichever roofline gives the longer time for this workload
         t_hbm = up_bytes / (HBM_PEAK_GBS * 1e9)
         t_mfma = 4.0 * d * f * A / (MFMA_BF16_PEAK_TFLOPS * 1e12)
-        traffic = measured_traffic(args.workload, "up")
+        traffic = measured_traffic(args.workload, "up") if args.tokens is None else None
         if t_hbm >= t_mfma:
             roof = {"bound": "hbm", "achieved": up_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": up_gbs / HBM_PEAK_GBS, "traffic": traffic}

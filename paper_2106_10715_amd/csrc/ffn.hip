@@ -729,9 +729,10 @@ __global__ __launch_bounds__(256) void ffn_mfma_kernel(const uint16_t* __restric
         const void* wave_w = reinterpret_cast<const void*>((static_cast<uintptr_t>(wb_hi) << 32) | static_cast<uintptr_t>(wb_lo));
         // The sweep over the reduction dimension starts at a step that depends on the expert and on the
         // chunk of 8 column groups only: blocks that share a weight stream or an activation tile walk it
-        // together, other blocks are out of step with them.
+        // together; neighbouring chunks are one step apart (measured: far-apart chunks fetch the activation
+        // tile again, chunks in step collide on their weight streams), other experts anywhere.
         const unsigned col_chunk = static_cast<unsigned>(block_y) >> ((GATED || NF == 2) ? 3 : 4);   // same for both unit widths
-        const unsigned key = static_cast<unsigned>(e) * 37u + col_chunk * 17u;
+        const unsigned key = static_cast<unsigned>(e) * 37u + col_chunk;
         switch ((rows + 31) >> 5) {
             case 1: ffn_tile<GATED, NF, 1>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave); break;
             case 2: ffn_tile<GATED, NF, 2>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave); break;

@@ -312,6 +312,73 @@ __global__ __launch_bounds__(256) void gate_prep_kernel(const uint16_t* __restri
     }
 }
 
+// ---- wave-wide reductions in the lanes' own registers: an inclusive scan by row shifts, then row
+// broadcasts, leaves the total in lane 63 (a dozen vector instructions; a butterfly of lane exchanges goes
+// through the LDS permute unit six times, some hundred cycles each, and the selection is a chain of them).
+template <int CTRL, int ROW_MASK>
+__device__ inline unsigned dpp_from(unsigned identity, unsigned v) {
+    return static_cast<unsigned>(__builtin_amdgcn_update_dpp(static_cast<int>(identity), static_cast<int>(v), CTRL, ROW_MASK, 0xf, false));
+}
+__device__ inline unsigned wave_max_u32(unsigned v) {
+    v = max(v, dpp_from<0x111, 0xf>(0u, v));      // row_shr:1
+    v = max(v, dpp_from<0x112, 0xf>(0u, v));      // row_shr:2
+    v = max(v, dpp_from<0x114, 0xf>(0u, v));      // row_shr:4
+    v = max(v, dpp_from<0x118, 0xf>(0u, v));      // row_shr:8: lane 15 of every row of 16 holds the row's maximum
+    v = max(v, dpp_from<0x142, 0xa>(0u, v));      // row_bcast:15 into rows 1 and 3
+    v = max(v, dpp_from<0x143, 0xc>(0u, v));      // row_bcast:31 into rows 2 and 3: lane 63 holds the wave's
+    return static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(v), 63));
+}
+__device__ inline unsigned wave_min_u32(unsigned v) { return ~wave_max_u32(~v); }
+__device__ inline float wave_sum_f32(float x) {
+    auto step = [](float v, unsigned got) { return v + __uint_as_float(got); };
+    x = step(x, dpp_from<0x111, 0xf>(0u, __float_as_uint(x)));
+    x = step(x, dpp_from<0x112, 0xf>(0u, __float_as_uint(x)));
+    x = step(x, dpp_from<0x114, 0xf>(0u, __float_as_uint(x)));
+    x = step(x, dpp_from<0x118, 0xf>(0u, __float_as_uint(x)));
+    x = step(x, dpp_from<0x142, 0xa>(0u, __float_as_uint(x)));
+    x = step(x, dpp_from<0x143, 0xc>(0u, __float_as_uint(x)));
+    return __uint_as_float(static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(__float_as_uint(x)), 63)));
+}
+// fp32 values as unsigned keys of the same order (finite values; -0 must have been turned into +0)
+__device__ inline unsigned order_key(float v) {
+    const unsigned u = __float_as_uint(v);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ inline float from_order_key(unsigned key) {
+    return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
+}
+
+// Exact value (products exact, sums in fp64) of column `col` of the projection of token t, by one wave, from
+// the packed fragments: lane j takes the 8-row pieces j, j + 64, ... of the column.  Every lane gets the sum.
+__device__ inline double exact_column_dot(const uint16_t* __restrict__ x, const uint4* __restrict__ pack, size_t t, int col,
+                                          int nS, int d, int lane) {
+    const int nb = col >> 5, cin = col & 31;
+    const uint4* xr = reinterpret_cast<const uint4*>(x + t * d);
+    double sum = 0.0;
+    for (int j = lane; j < nS * 8; j += 64) {
+        const int S = j >> 3, q = (j & 7) >> 1, h = j & 1;          // rows 64 S + 32 h + 8 q .. + 8
+        const uint4 wq = pack[((static_cast<size_t>(nb) * nS + S) * 4 + q) * 64 + h * 32 + cin];
+        const uint4 xq = xr[S * 8 + h * 4 + q];
+        const uint32_t xu[4] = {xq.x, xq.y, xq.z, xq.w}, wu[4] = {wq.x, wq.y, wq.z, wq.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            sum = fma(static_cast<double>(__uint_as_float(xu[i] << 16)), static_cast<double>(__uint_as_float(wu[i] << 16)), sum);
+            sum = fma(static_cast<double>(__uint_as_float(xu[i] & 0xffff0000u)),
+                      static_cast<double>(__uint_as_float(wu[i] & 0xffff0000u)), sum);
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
+    return sum;
+}
+
+constexpr int kMaxCand = 12;     // columns of one token that are re-evaluated one by one; more than that: all columns
+
+template <int NB>
+constexpr int gate_parts() { return NB <= 4 ? kGateWaves : 1; }      // one partial tile per wave while they fit the LDS
+template <int NB>
+constexpr size_t gate_tile_bytes() { return static_cast<size_t>(gate_parts<NB>()) * kGateTokens * (NB * 32 + 1) * sizeof(float); }
+
 template <int NB>
 __global__ __launch_bounds__(kGateWaves * 64) void route_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wg,
                                                          const uint4* __restrict__ pack, const float* __restrict__ part,
@@ -320,20 +387,42 @@ __global__ __launch_bounds__(kGateWaves * 64) void route_mfma_kernel(const uint1
                                                          int hash) {
     // hash: E is the number of sign bits (columns of the projection), one expert id per token, weight 1
     constexpr int EP = NB * 32;
-    __shared__ float logit[kGateTokens][EP + 1];
+    constexpr int kParts = gate_parts<NB>();
+    extern __shared__ float part_tile[];                   // [kParts][kGateTokens][EP + 1]: partial logit tiles
     __shared__ float xsq_w[kGateWaves][kGateTokens];
     __shared__ float wn2_sh;
     __shared__ int flagged[kGateTokens];
     __shared__ double resc[kGateWaves][EP];
+    auto tile_at = [&](int p, int tok, int e) -> float& { return part_tile[(p * kGateTokens + tok) * (EP + 1) + e]; };
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int t0 = blockIdx.x * kGateTokens;
     const int nS = d / 64;
 
+    // A wave's groups S = wave, wave + 8, ... are taken kAhead at a time: the token pieces of all of them are
+    // requested first (they come from HBM: one latency instead of one per group; the first batch is
+    // requested before the column norms below are worked out), the gate fragments, which every block re-reads
+    // from the L2, one or two groups ahead of the MFMAs that use them (as many as the registers of two waves
+    // per SIMD hold for this number of expert blocks).
+    constexpr int kAhead = NB <= 2 ? 4 : NB <= 4 ? 2 : 1;
+    constexpr int kRing = NB <= 1 ? 3 : 2;
+    const int row = min(t0 + (lane & 31), T - 1);
+    const uint4* xrow = reinterpret_cast<const uint4*>(x + static_cast<size_t>(row) * d + 32 * (lane >> 5));
+    uint4 xv[kAhead][4];
+    auto fetch_x = [&](int S0) {
+#pragma unroll
+        for (int p = 0; p < kAhead; ++p) {
+            const int S = S0 + p * kGateWaves < nS ? S0 + p * kGateWaves : 0;      // past the end: group 0, unused
+#pragma unroll
+            for (int q = 0; q < 4; ++q) xv[p][q] = xrow[S * 8 + q];                // 64 contiguous bytes of the token row
+        }
+    };
+    fetch_x(wave);
+
     // ---- largest column norm of W_g: fixed-order sum of the per-group parts, then the block maximum.
     // Thread (g, c) adds the parts S = g, g + G, ... of column c; thread c adds the G partial sums in order.
     {
-        __shared__ float colpart[kGateWaves * 64];
+        float* colpart = part_tile;                        // kGateWaves * 64 floats, free until the tiles are written
         constexpr int G = EP >= kGateWaves * 64 ? 1 : kGateWaves * 64 / EP;
         float best = 0.f;
         for (int c0 = 0; c0 < EP; c0 += kGateWaves * 64) {          // one round unless EP exceeds the block
@@ -350,8 +439,7 @@ __global__ __launch_bounds__(kGateWaves * 64) void route_mfma_kernel(const uint1
             }
             __syncthreads();
         }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) best = fmaxf(best, __shfl_xor(best, off));
+        best = __uint_as_float(wave_max_u32(__float_as_uint(best)));   // sums of squares: not negative, ordered like their bits
         if (lane == 0) xsq_w[wave][0] = best;
         __syncthreads();
         if (threadIdx.x == 0) {
@@ -368,79 +456,101 @@ __global__ __launch_bounds__(kGateWaves * 64) void route_mfma_kernel(const uint1
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[nb][v] = 0.f;
-    const int row = min(t0 + (lane & 31), T - 1);
-    const uint4* xrow = reinterpret_cast<const uint4*>(x + static_cast<size_t>(row) * d + 32 * (lane >> 5));
     float xs = 0.f;
-    // the loads of the next 64-element group are issued before the arithmetic of the current one
-    uint4 xa[4], wb[NB][4];
-    auto fetch = [&](int S, uint4 (&xv)[4], uint4 (&wv)[NB][4]) {
+    for (int S0 = wave; S0 < nS; S0 += kGateWaves * kAhead) {
+        if (S0 != wave) fetch_x(S0);
+        uint4 wv[kRing][NB][4];
+        auto fetch_w = [&](int p, uint4 (&dst)[NB][4]) {
+            const int S = S0 + p * kGateWaves < nS ? S0 + p * kGateWaves : S0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) xv[q] = xrow[S * 8 + q];          // 64 contiguous bytes of the token row
+            for (int nb = 0; nb < NB; ++nb) {
+                const uint4* bp = pack + ((static_cast<size_t>(nb) * nS + S) * 4) * 64 + lane;
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const uint4* bp = pack + ((static_cast<size_t>(nb) * nS + S) * 4) * 64 + lane;
+                for (int q = 0; q < 4; ++q) dst[nb][q] = bp[q * 64];
+            }
+        };
 #pragma unroll
-            for (int q = 0; q < 4; ++q) wv[nb][q] = bp[q * 64];
-        }
-    };
-    if (wave < nS) fetch(wave, xa, wb);
-    for (int S = wave; S < nS; S += kGateWaves) {
-        uint4 xn[4], wn[NB][4];
-        fetch(S + kGateWaves < nS ? S + kGateWaves : S, xn, wn);                        // past the end: the same group again, unused
+        for (int p = 0; p + 1 < kRing; ++p) fetch_w(p, wv[p]);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const uint32_t u[4] = {xa[q].x, xa[q].y, xa[q].z, xa[q].w};
+        for (int p = 0; p < kAhead; ++p) {
+            if (p + kRing - 1 < kAhead) fetch_w(p + kRing - 1, wv[(p + kRing - 1) % kRing]);
+            if (S0 + p * kGateWaves < nS) {                                        // uniform for the wave
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float lo = __uint_as_float(u[i] << 16), hi = __uint_as_float(u[i] & 0xffff0000u);
-                xs = fmaf(lo, lo, xs);
-                xs = fmaf(hi, hi, xs);
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t u[4] = {xv[p][q].x, xv[p][q].y, xv[p][q].z, xv[p][q].w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float lo = __uint_as_float(u[i] << 16), hi = __uint_as_float(u[i] & 0xffff0000u);
+                        xs = fmaf(lo, lo, xs);
+                        xs = fmaf(hi, hi, xs);
+                    }
+                }
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xv[p][q]),
+                                                                           __builtin_bit_cast(bf16x8, wv[p % kRing][nb][q]), acc[nb], 0, 0, 0);
             }
         }
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, xa[q]),
-                                                                   __builtin_bit_cast(bf16x8, wb[nb][q]), acc[nb], 0, 0, 0);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) xa[q] = xn[q];
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) wb[nb][q] = wn[nb][q];
     }
     xs += __shfl_xor(xs, 32);
     if (lane < 32) xsq_w[wave][lane] = xs;
-    // partial tiles are added in wave order: ((w0 + w1) + w2) + ...
-    for (int turn = 0; turn < kGateWaves; ++turn) {
-        if (wave == turn) {
+    // The partial tiles are added in wave order, ((w0 + w1) + w2) + ...: by the lane that reads a logit when
+    // every wave has a tile of its own, else wave after wave into one tile.
+    if (kParts == kGateWaves) {
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int tok = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), e = 32 * nb + (lane & 31);
-                    logit[tok][e] = turn == 0 ? acc[nb][v] : logit[tok][e] + acc[nb][v];
-                }
-        }
+            for (int v = 0; v < 16; ++v)
+                tile_at(wave, 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), 32 * nb + (lane & 31)) = acc[nb][v];
         __syncthreads();
+    } else {
+        for (int turn = 0; turn < kGateWaves; ++turn) {
+            if (wave == turn) {
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        float& at = tile_at(0, 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), 32 * nb + (lane & 31));
+                        at = turn == 0 ? acc[nb][v] : at + acc[nb][v];
+                    }
+            }
+            __syncthreads();
+        }
     }
 
-    // ---- selection: wave w ranks tokens w, w+4, ...
+    // ---- selection: wave w ranks tokens w, w + 8, ...
     const int n_chain = ((nS + kGateWaves - 1) / kGateWaves) * 4;                               // MFMAs a wave chains per logit
     const double gamma = 1.0625 * 5.9604644775390625e-8 * static_cast<double>(17 * n_chain + 8);
+    constexpr int NE = (NB + 1) / 2;         // experts a lane holds: eg, eg + 64, ... (kNE at most)
     const int eg = lane;
     const int kk_sel = min(k + 1, E);
     float bl[kNE];
 #pragma unroll
-    for (int i = 0; i < kNE; ++i) bl[i] = (bias != nullptr && eg + 64 * i < E) ? bias[eg + 64 * i] : 0.f;
+    for (int i = 0; i < kNE; ++i) bl[i] = i >= NE ? 0.f : (bias != nullptr && eg + 64 * i < E) ? bias[eg + 64 * i] : 0.f;
     const double wn2 = static_cast<double>(wn2_sh);
     for (int tt = wave; tt < kGateTokens; tt += kGateWaves) {
         const int t = t0 + tt;
         if (t >= T) { if (lane == 0) flagged[tt] = 0; continue; }
-        double lv[kNE];
+        // this lane's logits, fp32 (a -0 becomes +0: equal logits must compare equal) and as ordered keys
+        float fv[NE];
+        unsigned key[NE];
 #pragma unroll
-        for (int i = 0; i < kNE; ++i) lv[i] = eg + 64 * i < E ? static_cast<double>(logit[tt][eg + 64 * i] + bl[i]) : 0.0;
+        for (int i = 0; i < NE; ++i) {
+            const int ei = eg + 64 * i;
+            const int ec = ei < E ? ei : 0;                 // lanes without an expert read column 0 and drop it
+            float sum = tile_at(0, tt, ec);
+            if (kParts > 1) {
+#pragma unroll
+                for (int pw = 1; pw < kParts; ++pw) sum += tile_at(pw, tt, ec);
+            }
+            fv[i] = ei < E ? (sum + bl[i]) + 0.0f : 0.f;
+            key[i] = ei < E ? order_key(fv[i]) : 0u;
+        }
+        double lv[kNE];                          // entries from NE on belong to no expert and are never looked at
+#pragma unroll
+        for (int i = 0; i < kNE; ++i) lv[i] = i < NE ? static_cast<double>(fv[i < NE ? i : 0]) : 0.0;
         double sv[kSel];
         int se[kSel];
         int code = 0;
@@ -448,7 +558,22 @@ __global__ __launch_bounds__(kGateWaves * 64) void route_mfma_kernel(const uint1
         if (hash) {
             sign_bits(lv, eg, true, E, code, gap, vmax);
         } else {
-            wave_topk(lv, eg, true, E, kk_sel, sv, se);
+            // rank by rank: the largest key of the wave, then the lowest expert that has it
+            unsigned taken = 0;
+#pragma unroll
+            for (int r = 0; r < kSel; ++r) {
+                if (r < kk_sel) {
+                    unsigned bk = 0u, be = 0xffffffffu;
+#pragma unroll
+                    for (int i = 0; i < NE; ++i)
+                        if (eg + 64 * i < E && !((taken >> i) & 1u) && key[i] > bk) { bk = key[i]; be = static_cast<unsigned>(eg + 64 * i); }
+                    const unsigned top = wave_max_u32(bk);
+                    const unsigned who = wave_min_u32(bk == top ? be : 0xffffffffu);
+                    sv[r] = static_cast<double>(from_order_key(top));
+                    se[r] = static_cast<int>(who);
+                    if ((who & 63u) == static_cast<unsigned>(eg)) taken |= 1u << (who >> 6);
+                }
+            }
             rank_gaps(sv, kk_sel, gap, vmax);
         }
         float xn2f = xsq_w[0][tt];
@@ -456,23 +581,81 @@ __global__ __launch_bounds__(kGateWaves * 64) void route_mfma_kernel(const uint1
         const double xn2 = static_cast<double>(xn2f);
         const double delta = gamma * sqrt(xn2 * wn2) + 1.0625 * 5.9604644775390625e-8 * vmax;
         const bool close = gap <= 2.0 * delta;
-        if (lane == 0) flagged[tt] = close ? 1 : 0;
         if (!close) {
+            if (lane == 0) flagged[tt] = 0;
             if (hash) {
                 if (lane == 0) { idx[t] = code; w[t] = 1.f; }
             } else {
-                emit_token(lv, sv, se, eg, true, E, k, renorm, lane, idx + static_cast<size_t>(t) * k, w + static_cast<size_t>(t) * k);
+                float wj[kSel];
+                float denom = 0.f;
+#pragma unroll
+                for (int r = 0; r < kSel; ++r)
+                    if (r < k) wj[r] = expf(static_cast<float>(sv[r] - sv[0]));
+                if (renorm) {
+#pragma unroll
+                    for (int r = 0; r < kSel; ++r)
+                        if (r < k) denom += wj[r];
+                } else {
+                    float part_sum = 0.f;
+#pragma unroll
+                    for (int i = 0; i < NE; ++i)
+                        if (eg + 64 * i < E) part_sum += expf(static_cast<float>(lv[i] - sv[0]));
+                    denom = wave_sum_f32(part_sum);
+                }
+                if (lane == 0) {
+#pragma unroll
+                    for (int r = 0; r < kSel; ++r)
+                        if (r < k) {
+                            idx[static_cast<size_t>(t) * k + r] = se[r];
+                            w[static_cast<size_t>(t) * k + r] = wj[r] / denom;
+                        }
+                }
             }
+            continue;
+        }
+        // Too close to call in fp32.  Which columns can exact arithmetic still change the answer for?
+        // Top-k: every logit within 2 delta of the (k+1)-th best, or above it (anything lower stays below
+        // all of those even with both errors against it).  Sign bits: every projection within 2 delta of
+        // zero.  Usually two or three columns: each is one exact dot product by this wave; the other
+        // columns keep their fp32 values, which cannot reach the selected ones.
+        const double reach = hash ? 2.0 * delta : sv[kk_sel - 1] - 2.0 * delta;
+        unsigned long long in_reach[NE];
+        int count = 0;
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+            in_reach[i] = __ballot(eg + 64 * i < E && (hash ? fabs(lv[i]) <= reach : lv[i] >= reach));
+            count += __popcll(in_reach[i]);
+        }
+        if (lane == 0) flagged[tt] = count > kMaxCand ? 1 : 0;
+        if (count > kMaxCand) continue;                                  // all columns, by the whole block, below
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+            unsigned long long m = in_reach[i];
+            while (m != 0ull) {                                          // uniform for the wave
+                const int l = __ffsll(static_cast<long long>(m)) - 1;
+                m &= m - 1ull;
+                const double exact = exact_column_dot(x, pack, static_cast<size_t>(t), l + 64 * i, nS, d, lane);
+                if (eg == l) lv[i] = exact + static_cast<double>(bl[i]);
+            }
+        }
+        if (hash) {
+            sign_bits(lv, eg, true, E, code, gap, vmax);
+            if (lane == 0) { idx[t] = code; w[t] = 1.f; }
+        } else {
+            wave_topk(lv, eg, true, E, kk_sel, sv, se);
+            emit_token(lv, sv, se, eg, true, E, k, renorm, lane, idx + static_cast<size_t>(t) * k, w + static_cast<size_t>(t) * k);
         }
     }
     __syncthreads();
 
-    // ---- fp64 re-evaluation of the tokens that were too close to call, by the whole block, from the
+    // ---- tokens with more columns in reach than that: all columns in fp64, by the whole block, from the
     // same packed fragments and with the same split as the MFMA pass: wave w takes the groups
     // S = w, w+8, ..., lane (c, h) the 32 rows 64 S + 32 h .. of column c of every expert block; the two
     // halves are added by a lane exchange, the waves in wave order.
-    for (int tt = 0; tt < kGateTokens; ++tt) {
-        if (!flagged[tt]) continue;                                      // uniform for the block
+    unsigned long long todo = __ballot(lane < kGateTokens && flagged[lane & (kGateTokens - 1)] != 0);   // the same in every wave
+    while (todo != 0ull) {
+        const int tt = __ffsll(static_cast<long long>(todo)) - 1;
+        todo &= todo - 1ull;
         const int t = t0 + tt;
         const uint4* xr = reinterpret_cast<const uint4*>(x + static_cast<size_t>(t) * d + 32 * (lane >> 5));
         double a64[NB];
@@ -562,9 +745,17 @@ int launch_route(const moe_cfg& c, const void* x, const void* Wg, const float* b
                            pack, part);
         MOE_LAUNCH_CHECK("gate_prep_kernel");
         dim3 grid((c.T + kGateTokens - 1) / kGateTokens), block(kGateWaves * 64);
+        int dev = 0;
+        MOE_HIP_CHECK(hipGetDevice(&dev));
 #define MOE_ROUTE_CASE(N)                                                                                             \
     case N:                                                                                                           \
-        hipLaunchKernelGGL(route_mfma_kernel<N>, grid, block, 0, s, static_cast<const uint16_t*>(x),                   \
+        if (static int raised_on = -1; raised_on != dev) {     /* the tiles of 64 experts and more exceed the default */ \
+            MOE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&route_mfma_kernel<N>),                   \
+                                              hipFuncAttributeMaxDynamicSharedMemorySize,                             \
+                                              static_cast<int>(gate_tile_bytes<N>())));                               \
+            raised_on = dev;                                                                                          \
+        }                                                                                                             \
+        hipLaunchKernelGGL(route_mfma_kernel<N>, grid, block, gate_tile_bytes<N>(), s, static_cast<const uint16_t*>(x), \
                            static_cast<const uint16_t*>(Wg), pack, part, bias, idx, w, c.T, c.d, cols, c.k, c.renorm, \
                            hash);                                                                                     \
         break;
