@@ -61,6 +61,8 @@ ROUTE_CASES = [
     (50, 64, 256, 4, "bf16", 1, True),
     (33, 4096, 32, 1, "bf16", 1, False),       # the paper's width
     (19, 320, 8, 8, "f32", 1, True),           # k = E
+    (90, 256, 100, 2, "bf16", 0, True),        # four expert blocks: the largest per-wave partial tiles (dynamic LDS)
+    (40, 128, 160, 3, "bf16", 1, False),       # five expert blocks: one shared tile, waves add in turn
 ]
 
 
@@ -96,6 +98,29 @@ def test_route_ties_and_near_ties(dtype):
     assert rel_l2(w, ref.w) <= 1e-5
     # the case is only meaningful if some decisions really were inside fp32 noise
     assert (ref.margin < 1e-6).sum() >= 2
+
+
+@pytest.mark.parametrize("E,k", [(40, 2), (200, 8)])
+def test_route_many_columns_too_close_to_call(E, k):
+    """More tied columns than the gate re-evaluates one by one (twenty identical experts, and tokens that are
+    all zero): the block-wide fp64 pass decides, ties still go to the lower expert index."""
+    T, d = 70, 256
+    x, Wg, _ = make_inputs(11, T, d, E, "bf16")
+    for e in range(3, 23):
+        Wg[:, e] = Wg[:, 3]
+    x[5] = 0.0
+    x[69] = 0.0
+    cfg = M.MoeCfg.make(T, d, 64, E, k, "bf16")
+    idx, w = gpu_route(cfg, x, Wg, None, "bf16")
+    ref = O.route(x, Wg, k)
+    assert np.array_equal(idx, ref.idx)
+    assert idx[5].tolist() == list(range(k)) and idx[69].tolist() == list(range(k))
+    assert rel_l2(w, ref.w) <= 1e-5
+    # some tokens select the twenty twins: they must come out as expert 3, then 4, ...
+    assert (idx == 3).any()
+    for j in range(k - 1):
+        sel = (idx[:, j] >= 3) & (idx[:, j] < 22)
+        assert np.all(idx[sel, j + 1] == idx[sel, j] + 1)
 
 
 @pytest.mark.parametrize("T,d,bits,dtype", [(64, 256, 2, "f32"), (257, 512, 5, "bf16"), (130, 192, 8, "bf16"),
