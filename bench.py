@@ -266,6 +266,45 @@ def main():
         out["streaming"] = {"h2d_gbs": h2d, "copy_window_ms": cm, "step_ms": ms_per_step,
                             "copy_share_of_step": cm / ms_per_step,
                             "experts_loaded_per_step": float(np.mean(loaded))}
+        if not args.keep_experts:
+            # Overlap of loading and computing (Section 6.2: separate streams so that the two run side by
+            # side): the same copies alone (back to back on a side stream, nothing else running), the same
+            # layer alone (experts resident), and how much of the shorter of the two the streamed step hides.
+            live_experts = [int(e) for e in np.nonzero(counts)[0]]
+            side = torch.cuda.Stream()
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            alone_ms = []
+            for _ in range(3):
+                torch.cuda.synchronize()
+                with torch.cuda.stream(side):
+                    ev0.record(side)
+                    for i, e in enumerate(live_experts):
+                        slots[i % args.slots].copy_(L.host_packed[e], non_blocking=True)
+                    ev1.record(side)
+                ev1.synchronize()
+                alone_ms.append(ev0.elapsed_time(ev1))
+            copy_alone_ms = float(np.mean(alone_ms[1:]))
+            resident = torch.empty((wl.E, eb), dtype=torch.uint8, device="cuda")
+            resident.copy_(L.host_packed)
+            torch.cuda.synchronize()
+            for _ in range(3):
+                M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, resident, None, L.y, L.ws)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(10):
+                M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, resident, None, L.y, L.ws)
+            torch.cuda.synchronize()
+            compute_alone_ms = (time.perf_counter() - t1) * 1e3 / 10
+            del resident
+            shorter = min(copy_alone_ms, compute_alone_ms)
+            out["streaming"].update({
+                "copy_alone_ms": copy_alone_ms, "copy_alone_gbs": len(live_experts) * eb / (copy_alone_ms * 1e-3) / 1e9,
+                "compute_alone_ms": compute_alone_ms,
+                "exposed_ms": ms_per_step - copy_alone_ms,
+                "overlap": (copy_alone_ms + compute_alone_ms - ms_per_step) / shorter,
+                "overlap_note": "(copies alone + layer alone - streamed step) / the shorter of the two; 1 = the shorter one is hidden "
+                                "completely; the streamed step also holds the routing that must precede the first load",
+                "h2d_frac_of_copies_alone": h2d / (len(live_experts) * eb / (copy_alone_ms * 1e-3) / 1e9)})
         if args.order == "greedy":
             order, ok = ctx.last_order()
             out["streaming"].update({"order_first": order[:8], "order_last": order[-4:], "constraints_satisfiable": ok})
