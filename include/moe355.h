@@ -129,7 +129,10 @@ int moe_combine(const moe_cfg* cfg, const void* Yp, const int32_t* inv, const fl
 
 /*
  * The whole layer, x -> y, as route -> permute -> expert FFNs -> combine on `stream`; every
- * intermediate lives in ws.
+ * intermediate lives in ws.  When every token has one expert with weight exactly 1 (bf16, k = 1 and
+ * renorm = 1 or the hashing gate: the paper's layer) the combine step is only a row permutation, and
+ * the down-projection writes its rows to their tokens' rows of y itself instead of a separate pass; the
+ * bytes of y are the same as from the four steps called one by one.
  *   Resident mode (sctx == NULL): W_packed holds all E packed experts on the device; nothing waits
  *   on the host.
  *   Streamed mode (sctx != NULL, W_packed ignored): the experts live in pinned host memory (Section 6).

@@ -219,6 +219,14 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
     size_t eb = 0;
     moe_expert_bytes(cfg, &eb);
 
+    // One expert per token with weight exactly 1 (top-1 with weights renormalised over the selection, or the
+    // hashing gate): the combine step would only move row inv[t] of the batched results to row t.  The
+    // down-projection then stores its rows at their tokens' places itself (perm[r] is the token of batched
+    // row r) and the combine kernel is not run; the bytes written are the same ones.
+    const bool direct = c.dtype == MOE_BF16 && c.k == 1 && (c.renorm == 1 || c.gate == MOE_GATE_HASH);
+    void* ffn_out = direct ? y : static_cast<void*>(base + L.Yp);
+    const int32_t* row_map = direct ? perm : nullptr;
+
     hipEvent_t* tev = nullptr;     // this call's stage events, if stage timing is on and has room
     if (sctx == nullptr && g_timer.on && g_timer.n < g_timer.cap) tev = g_timer.ev + kStageEvents * g_timer.n++;
     const bool all_stages = tev != nullptr && !g_timer.up_only;
@@ -231,9 +239,9 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
     if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[2], s));
 
     if (sctx == nullptr) {
-        if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, 0, c.E, W_packed, eb, A, base + L.H, base + L.Yp,
+        if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, 0, c.E, W_packed, eb, A, base + L.H, ffn_out,
                                        reinterpret_cast<int32_t*>(base + L.ffn_plan), s, tev ? tev[3] : nullptr,
-                                       tev && g_timer.up_only ? tev[2] : nullptr))
+                                       tev && g_timer.up_only ? tev[2] : nullptr, row_map))
             return rc;
         if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[4], s));
     } else {
@@ -274,8 +282,8 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
             // Everything this call needs is resident and the slots are laid out like a resident expert array:
             // one launch over all experts instead of one per expert.
             for (int pos = 0; pos < n_order; ++pos) MOE_HIP_CHECK(hipStreamWaitEvent(s, sctx->loaded[slot_of[pos]], 0));
-            if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, 0, c.E, sctx->dev_slots, eb, A, base + L.H, base + L.Yp,
-                                           reinterpret_cast<int32_t*>(base + L.ffn_plan), s))
+            if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, 0, c.E, sctx->dev_slots, eb, A, base + L.H, ffn_out,
+                                           reinterpret_cast<int32_t*>(base + L.ffn_plan), s, nullptr, nullptr, row_map))
                 return rc;
             for (int pos = 0; pos < n_order; ++pos) {
                 MOE_HIP_CHECK(hipEventRecord(sctx->released[slot_of[pos]], s));
@@ -305,8 +313,8 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
                 ++i;
             }
             MOE_HIP_CHECK(hipStreamWaitEvent(s, sctx->loaded[slot], 0));   // also when kept: its load may still be running
-            if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, e, 1, dst, eb, n_e, base + L.H, base + L.Yp,
-                                           reinterpret_cast<int32_t*>(base + L.ffn_plan), s))
+            if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, e, 1, dst, eb, n_e, base + L.H, ffn_out,
+                                           reinterpret_cast<int32_t*>(base + L.ffn_plan), s, nullptr, nullptr, row_map))
                 return rc;
             MOE_HIP_CHECK(hipEventRecord(sctx->released[slot], s));
             sctx->released_valid[slot] = true;
@@ -317,7 +325,8 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
             sctx->timed = i > 0;
         }
     }
-    if (int rc = launch_combine(c, base + L.Yp, inv, w, y, s)) return rc;
+    if (!direct)
+        if (int rc = launch_combine(c, base + L.Yp, inv, w, y, s)) return rc;
     if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[5], s));
     return MOE_OK;
 }

@@ -73,7 +73,10 @@ int launch_pack(const moe_cfg& c, const void* Win, const void* Wgate, const void
 // `before_up`, if not null, right before the up kernel.
 int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, int e_first, int e_count,
                       const void* W, size_t expert_stride_bytes, long max_rows, void* H, void* Yp, int32_t* plan,
-                      hipStream_t s, hipEvent_t between = nullptr, hipEvent_t before_up = nullptr);
+                      hipStream_t s, hipEvent_t between = nullptr, hipEvent_t before_up = nullptr,
+                      const int32_t* row_map = nullptr);
+// row_map (bf16 only): row r of the batched order is written to row row_map[r] of Yp instead of row r, which
+// turns the down-projection's output into the layer's output when no weighting follows (see moe_layer_forward).
 // `plan`: ffn_plan_bytes(c) bytes of workspace, rewritten by every launch_expert_ffn (room for ffn_plan_tiles(c) row tiles).
 size_t ffn_plan_tiles(const moe_cfg& c);
 size_t ffn_plan_bytes(const moe_cfg& c);

@@ -414,7 +414,7 @@ __device__ inline unsigned thread_id(int wave) {
 template <bool GATED, int NF, int MBS>
 __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_t* __restrict__ A, int row_begin, int rows,
                                 const void* wave_base, uint16_t* __restrict__ C, int K, int N, int unit,
-                                bool active, int act, unsigned phase_key, int wave_s) {
+                                bool active, int act, unsigned phase_key, int wave_s, const int32_t* __restrict__ row_map) {
     unsigned tid = thread_id(wave_s);
     const int lane = tid & 63;
     // every tile height gets its own copy of the loop bounds: shared ones would be computed once for all
@@ -597,7 +597,10 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
             uint16_t* cbase = C + static_cast<size_t>(out_unit) * W + (seg % W);
             for (int r = tid / kLanesPerRow; r < kRowsPerPass && p0 + r < rows; r += kRowsPerIter) {
                 const uint4 val = *reinterpret_cast<const uint4*>(tile + r * kTileRowBytes + seg * 2);
-                *reinterpret_cast<uint4*>(cbase + static_cast<size_t>(row_begin + p0 + r) * N) = val;
+                // row_map: where each row of the batched order goes (the layer's output rows, when the rows
+                // need no weighting afterwards); none: the batched order itself
+                const int out_row = row_map != nullptr ? row_map[row_begin + p0 + r] : row_begin + p0 + r;
+                *reinterpret_cast<uint4*>(cbase + static_cast<size_t>(out_row) * N) = val;
             }
         }
     }
@@ -670,7 +673,7 @@ __global__ __launch_bounds__(256) void ffn_mfma_kernel(const uint16_t* __restric
                                                        int counter_base, int e_first, const char* __restrict__ W,
                                                        size_t expert_stride_bytes, size_t block_offset_bytes,
                                                        uint16_t* __restrict__ C, int K, int N, int act, int y_chunks,
-                                                       int mt_shift) {
+                                                       int mt_shift, const int32_t* __restrict__ row_map) {
     __shared__ uint4 lds[2][kTileM * kLdsRow];     // 2 x 36 KiB activation tiles, padded rows
     __shared__ int sh_q, sh_x;
     const int tiles = plan[16];
@@ -734,14 +737,14 @@ __global__ __launch_bounds__(256) void ffn_mfma_kernel(const uint16_t* __restric
         const unsigned col_chunk = static_cast<unsigned>(block_y) >> ((GATED || NF == 2) ? 3 : 4);   // same for both unit widths
         const unsigned key = static_cast<unsigned>(e) * 37u + col_chunk;
         switch ((rows + 31) >> 5) {
-            case 1: ffn_tile<GATED, NF, 1>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave); break;
-            case 2: ffn_tile<GATED, NF, 2>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave); break;
-            case 3: ffn_tile<GATED, NF, 3>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave); break;
-            case 4: ffn_tile<GATED, NF, 4>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave); break;
-            case 5: ffn_tile<GATED, NF, 5>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave); break;
-            case 6: ffn_tile<GATED, NF, 6>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave); break;
-            case 7: ffn_tile<GATED, NF, 7>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave); break;
-            default: ffn_tile<GATED, NF, 8>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave); break;
+            case 1: ffn_tile<GATED, NF, 1>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+            case 2: ffn_tile<GATED, NF, 2>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+            case 3: ffn_tile<GATED, NF, 3>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+            case 4: ffn_tile<GATED, NF, 4>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+            case 5: ffn_tile<GATED, NF, 5>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+            case 6: ffn_tile<GATED, NF, 6>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+            case 7: ffn_tile<GATED, NF, 7>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+            default: ffn_tile<GATED, NF, 8>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
         }
     }
 }
@@ -844,7 +847,7 @@ int launch_pack(const moe_cfg& c, const void* Win, const void* Wgate, const void
 
 int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, int e_first, int e_count,
                       const void* W, size_t expert_stride_bytes, long max_rows, void* H, void* Yp, int32_t* plan,
-                      hipStream_t s, hipEvent_t between, hipEvent_t before_up) {
+                      hipStream_t s, hipEvent_t between, hipEvent_t before_up, const int32_t* row_map) {
     if (max_rows <= 0 || e_count <= 0) return MOE_OK;
     const size_t df = static_cast<size_t>(c.d) * c.f;
     if (c.dtype == MOE_BF16) {
@@ -877,7 +880,7 @@ int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, 
         if (items > 0x7fffffffL) return fail(MOE_ERR_UNSUPPORTED, "too many work items for one launch (%ld)", items);
         hipLaunchKernelGGL((ffn_mfma_kernel<true, 2>), grid_for(items), block, 0, s, static_cast<const uint16_t*>(Xp), plan, 0,
                            e_first, static_cast<const char*>(W), expert_stride_bytes, size_t(0), static_cast<uint16_t*>(H),
-                           c.d, c.f, c.act, yc, mt_shift);
+                           c.d, c.f, c.act, yc, mt_shift, static_cast<const int32_t*>(nullptr));
         MOE_LAUNCH_CHECK("ffn_mfma_kernel<up>");
         if (between != nullptr) MOE_HIP_CHECK(hipEventRecord(between, s));
         // down-projection: narrow (32-column) units when wide ones would leave compute units idle
@@ -888,11 +891,11 @@ int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, 
         if (narrow)
             hipLaunchKernelGGL((ffn_mfma_kernel<false, 1>), grid_for(items), block, 0, s, static_cast<const uint16_t*>(H), plan, 8,
                                e_first, static_cast<const char*>(W), expert_stride_bytes, down_off, static_cast<uint16_t*>(Yp),
-                               c.f, c.d, c.act, yc, mt_shift);
+                               c.f, c.d, c.act, yc, mt_shift, row_map);
         else
             hipLaunchKernelGGL((ffn_mfma_kernel<false, 2>), grid_for(items), block, 0, s, static_cast<const uint16_t*>(H), plan, 8,
                                e_first, static_cast<const char*>(W), expert_stride_bytes, down_off, static_cast<uint16_t*>(Yp),
-                               c.f, c.d, c.act, yc, mt_shift);
+                               c.f, c.d, c.act, yc, mt_shift, row_map);
         MOE_LAUNCH_CHECK("ffn_mfma_kernel<down>");
         return MOE_OK;
     }
