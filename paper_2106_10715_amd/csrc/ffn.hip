@@ -181,27 +181,33 @@ template <int IMM>
 __device__ inline void ld_pinned(u32x4& dst, uint32_t voff, const void* sbase) {
     asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3" : "=v"(dst) : "v"(voff), "s"(sbase), "n"(IMM) : "memory");
 }
-// Same, marked non-temporal: the weights are read once, they should not push the activation tiles
-// (which every column group of an expert re-reads) out of the L2.
-template <int IMM>
+// The weight loads.  An expert with one row tile reads its weights once: marked non-temporal they do
+// not push the activation tiles (which every column group of the expert re-reads) out of the L2, and the
+// stream itself runs faster (a plain read stream of this shape reaches 6.2 TB/s, a non-temporal one 7.1).
+// An expert with several row tiles re-reads its weights once per tile: there the plain load, which leaves them
+// in the L2 for the tiles that follow, is the faster one (KEEP).
+template <int IMM, bool KEEP>
 __device__ inline void ld_pinned_stream(u32x4& dst, uint32_t voff, const void* sbase) {
-    asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3 nt" : "=v"(dst) : "v"(voff), "s"(sbase), "n"(IMM) : "memory");
+    if constexpr (KEEP)
+        asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3" : "=v"(dst) : "v"(voff), "s"(sbase), "n"(IMM) : "memory");
+    else
+        asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3 nt" : "=v"(dst) : "v"(voff), "s"(sbase), "n"(IMM) : "memory");
 }
 
 // The two fragments of one (column unit, k-step) are adjacent in the packed block:
 // [k-step][2][64 lanes] x 16 bytes (2 KiB per k-step); a wave with NF = 1 reads one of the two.
 // voff = byte offset of this lane inside its wave's stream at the first k-step of the pipeline step.
-template <int NF>
+template <bool KEEP, int NF>
 __device__ inline void load_b(BFrags<NF>& b, uint32_t voff, const void* wave_base) {
-    ld_pinned_stream<0>(b.v[0][0], voff, wave_base);
-    if (NF == 2) ld_pinned_stream<1024>(b.v[0][NF - 1], voff, wave_base);
-    ld_pinned_stream<2048>(b.v[1][0], voff, wave_base);
-    if (NF == 2) ld_pinned_stream<3072>(b.v[1][NF - 1], voff, wave_base);
+    ld_pinned_stream<0, KEEP>(b.v[0][0], voff, wave_base);
+    if (NF == 2) ld_pinned_stream<1024, KEEP>(b.v[0][NF - 1], voff, wave_base);
+    ld_pinned_stream<2048, KEEP>(b.v[1][0], voff, wave_base);
+    if (NF == 2) ld_pinned_stream<3072, KEEP>(b.v[1][NF - 1], voff, wave_base);
     const uint32_t voff2 = voff + 4096;
-    ld_pinned_stream<0>(b.v[2][0], voff2, wave_base);
-    if (NF == 2) ld_pinned_stream<1024>(b.v[2][NF - 1], voff2, wave_base);
-    ld_pinned_stream<2048>(b.v[3][0], voff2, wave_base);
-    if (NF == 2) ld_pinned_stream<3072>(b.v[3][NF - 1], voff2, wave_base);
+    ld_pinned_stream<0, KEEP>(b.v[2][0], voff2, wave_base);
+    if (NF == 2) ld_pinned_stream<1024, KEEP>(b.v[2][NF - 1], voff2, wave_base);
+    ld_pinned_stream<2048, KEEP>(b.v[3][0], voff2, wave_base);
+    if (NF == 2) ld_pinned_stream<3072, KEEP>(b.v[3][NF - 1], voff2, wave_base);
 }
 
 // Wait until at most N_YOUNGER loads are outstanding; the registers named become usable afterwards.
@@ -411,7 +417,7 @@ __device__ inline unsigned thread_id(int wave) {
 // to the last step) instead of being skipped, so every step issues the same loads.  Rows that are
 // clamped duplicates only produce output rows that are never stored (an output row depends on its own
 // input row only).
-template <bool GATED, int NF, int MBS>
+template <bool GATED, int NF, int MBS, bool KEEP>
 __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_t* __restrict__ A, int row_begin, int rows,
                                 const void* wave_base, uint16_t* __restrict__ C, int K, int N, int unit,
                                 bool active, int act, unsigned phase_key, int wave_s, const int32_t* __restrict__ row_map) {
@@ -464,7 +470,7 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
         ld_pinned<0>(dst.v[MBS - 1], a_last, base);
     };
     auto fetch_b = [&](BFrags<NF>& dst, int chunk) {
-        load_b(dst, static_cast<uint32_t>(chunk) * (kKS * 2048) + lane * 16, wave_base);
+        load_b<KEEP>(dst, static_cast<uint32_t>(chunk) * (kKS * 2048) + lane * 16, wave_base);
     };
     const uint32_t lane_off = lane * 16;
     // Blocks that share a weight stream or an activation tile start their sweep over the reduction
@@ -507,7 +513,7 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
         const uint32_t voff = static_cast<uint32_t>(at(min(ci + AD + 1, last))) * (kKS * 2048) + lane_off; \
         auto issue_b = [&](auto ic) {                                                                      \
             constexpr int i = decltype(ic)::value, ks = i / NF, j = i % NF;                                \
-            ld_pinned_stream<(ks & 1) * 2048 + j * 1024>(ring[((I) + AD + 1) % R].v[ks][j],                \
+            ld_pinned_stream<(ks & 1) * 2048 + j * 1024, KEEP>(ring[((I) + AD + 1) % R].v[ks][j],          \
                                                          voff + (ks >> 1) * 4096, wave_base);              \
         };                                                                                                 \
         run_step(acc, af, lds[ci & 1], lds[(ci + 1) & 1], ring[(I) % R], areg[((I) + 1) % AD],             \
@@ -612,8 +618,9 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
 // tiles and a small remainder.  Also clears the work counters of the two kernels that follow.
 //   plan[0..7], plan[8..15] : next work item of each of the 8 queues, up and down kernel
 //   plan[16]                : number of tiles
-//   plan[32 + 4 s ..]       : tile s = (expert, first row, rows, 0)
+//   plan[32 + 4 s ..]       : tile s = (expert, first row, rows, row tiles of this expert)
 constexpr int kPlanHeader = 32;
+constexpr int kKeepFromTiles = 2;       // row tiles of an expert from which its weights are worth keeping in the L2
 
 __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict__ offsets, int e_first, int e_count,
                                                        int tile_m, int32_t* __restrict__ plan, int total_rows, int max_tiles) {
@@ -647,7 +654,7 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
         const int per_tile = min(tile_m, ((my_n + my_tiles - 1) / my_tiles + 31) & ~31);
         int4* tiles = reinterpret_cast<int4*>(plan + kPlanHeader);
         for (int mt = 0; mt < my_tiles && start + mt < max_tiles; ++mt)
-            tiles[start + mt] = make_int4(e_first + mine, first[mine] + mt * per_tile, min(per_tile, my_n - mt * per_tile), 0);
+            tiles[start + mt] = make_int4(e_first + mine, first[mine] + mt * per_tile, min(per_tile, my_n - mt * per_tile), my_tiles);
     }
     if (t == 255) plan[16] = min(start + my_tiles, max_tiles);
     if (t < 16) plan[t] = 0;
@@ -714,7 +721,7 @@ __global__ __launch_bounds__(256) void ffn_mfma_kernel(const uint16_t* __restric
         if (slot >= tiles || block_y * 4 >= units) continue;   // past the last tile or column group (uniform)
         const int4 tile = tile_list[slot];         // the same for all lanes: kept in scalar registers
         const int e = __builtin_amdgcn_readfirstlane(tile.x), row_begin = __builtin_amdgcn_readfirstlane(tile.y),
-                  rows = __builtin_amdgcn_readfirstlane(tile.z);
+                  rows = __builtin_amdgcn_readfirstlane(tile.z), tiles_of_expert = __builtin_amdgcn_readfirstlane(tile.w);
 
         const int unit = block_y * 4 + wave;
         const bool active = unit < units;          // a wave past the last unit recomputes the last one, stores nothing
@@ -736,15 +743,29 @@ __global__ __launch_bounds__(256) void ffn_mfma_kernel(const uint16_t* __restric
         // tile again, chunks in step collide on their weight streams), other experts anywhere.
         const unsigned col_chunk = static_cast<unsigned>(block_y) >> ((GATED || NF == 2) ? 3 : 4);   // same for both unit widths
         const unsigned key = static_cast<unsigned>(e) * 37u + col_chunk;
-        switch ((rows + 31) >> 5) {
-            case 1: ffn_tile<GATED, NF, 1>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-            case 2: ffn_tile<GATED, NF, 2>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-            case 3: ffn_tile<GATED, NF, 3>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-            case 4: ffn_tile<GATED, NF, 4>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-            case 5: ffn_tile<GATED, NF, 5>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-            case 6: ffn_tile<GATED, NF, 6>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-            case 7: ffn_tile<GATED, NF, 7>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-            default: ffn_tile<GATED, NF, 8>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+        // weights of an expert with two row tiles or more are left in the L2 for its other tiles
+        if (tiles_of_expert >= kKeepFromTiles) {
+            switch ((rows + 31) >> 5) {
+                case 1: ffn_tile<GATED, NF, 1, true>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+                case 2: ffn_tile<GATED, NF, 2, true>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+                case 3: ffn_tile<GATED, NF, 3, true>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+                case 4: ffn_tile<GATED, NF, 4, true>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+                case 5: ffn_tile<GATED, NF, 5, true>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+                case 6: ffn_tile<GATED, NF, 6, true>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+                case 7: ffn_tile<GATED, NF, 7, true>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+                default: ffn_tile<GATED, NF, 8, true>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+            }
+        } else {
+            switch ((rows + 31) >> 5) {
+                case 1: ffn_tile<GATED, NF, 1, false>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+                case 2: ffn_tile<GATED, NF, 2, false>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+                case 3: ffn_tile<GATED, NF, 3, false>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+                case 4: ffn_tile<GATED, NF, 4, false>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+                case 5: ffn_tile<GATED, NF, 5, false>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+                case 6: ffn_tile<GATED, NF, 6, false>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+                case 7: ffn_tile<GATED, NF, 7, false>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+                default: ffn_tile<GATED, NF, 8, false>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
+            }
         }
     }
 }
