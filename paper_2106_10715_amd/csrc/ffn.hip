@@ -606,7 +606,11 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
                 // row_map: where each row of the batched order goes (the layer's output rows, when the rows
                 // need no weighting afterwards); none: the batched order itself
                 const int out_row = row_map != nullptr ? row_map[row_begin + p0 + r] : row_begin + p0 + r;
-                *reinterpret_cast<uint4*>(cbase + static_cast<size_t>(out_row) * N) = val;
+                // written once and next read by another kernel, after far more traffic than the L2 holds: stored
+                // non-temporal, so that the rows do not take the place of weights and activation tiles there
+                // (5 % of the layer's time at 128 tokens per expert)
+                __builtin_nontemporal_store(u32x4{val.x, val.y, val.z, val.w},
+                                            reinterpret_cast<u32x4*>(cbase + static_cast<size_t>(out_row) * N));
             }
         }
     }
