@@ -257,6 +257,9 @@ int moe_stage_timing_disable(void);
  * with the per-stage timing: enabling one replaces the other, moe_stage_timing_disable ends both.
  */
 int moe_up_kernel_timing_enable(int32_t max_calls);
+/* After enabling: time only the resident calls number 0, every, 2 every, ... from now on (up to max_calls of
+ * them), so that a long timed run pays the idle time of the two events in a fraction of its calls. */
+int moe_up_kernel_timing_every(int32_t every);
 int moe_up_kernel_timing_read(float* ms, int32_t capacity_calls, int32_t* n_calls);
 
 #ifdef __cplusplus

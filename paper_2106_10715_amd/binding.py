@@ -71,6 +71,7 @@ def lib() -> C.CDLL:
             "moe_stage_timing_read": [C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)],
             "moe_stage_timing_disable": [],
             "moe_up_kernel_timing_enable": [C.c_int32],
+            "moe_up_kernel_timing_every": [C.c_int32],
             "moe_up_kernel_timing_read": [C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)],
         }
         for name, args in sigs.items():
@@ -235,8 +236,10 @@ def moe_stage_timing_read(max_calls: int):
     return [{s: buf[c * len(STAGES) + i] for i, s in enumerate(STAGES)} for c in range(got)]
 
 
-def moe_up_kernel_timing_enable(max_calls: int) -> None:
+def moe_up_kernel_timing_enable(max_calls: int, every: int = 1) -> None:
     _check(lib().moe_up_kernel_timing_enable(max_calls))
+    if every != 1:
+        _check(lib().moe_up_kernel_timing_every(every))
 
 
 def moe_up_kernel_timing_read(max_calls: int):

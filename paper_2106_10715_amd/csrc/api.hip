@@ -104,6 +104,7 @@ struct StageTimer {
     bool on = false;
     bool up_only = false;         // only the two events around the up-projection kernel
     int cap = 0, n = 0;
+    int every = 1, seen = 0;      // calls seen since enabling; the calls 0, every, 2 every, ... are timed
     hipEvent_t* ev = nullptr;
 } g_timer;
 }  // namespace
@@ -228,7 +229,8 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
     const int32_t* row_map = direct ? perm : nullptr;
 
     hipEvent_t* tev = nullptr;     // this call's stage events, if stage timing is on and has room
-    if (sctx == nullptr && g_timer.on && g_timer.n < g_timer.cap) tev = g_timer.ev + kStageEvents * g_timer.n++;
+    if (sctx == nullptr && g_timer.on && g_timer.n < g_timer.cap && g_timer.seen++ % g_timer.every == 0)
+        tev = g_timer.ev + kStageEvents * g_timer.n++;
     const bool all_stages = tev != nullptr && !g_timer.up_only;
     if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[0], s));
     if (int rc = launch_route(c, x, W_g, gate_bias, idx, w, base + L.route, s)) return rc;
@@ -353,6 +355,14 @@ int moe_stage_timing_enable(int32_t max_calls) {
 int moe_up_kernel_timing_enable(int32_t max_calls) {
     if (int rc = moe_stage_timing_enable(max_calls)) return rc;
     g_timer.up_only = true;
+    return MOE_OK;
+}
+
+int moe_up_kernel_timing_every(int32_t every) {
+    if (!g_timer.on || !g_timer.up_only) return fail(MOE_ERR_INVALID_ARG, "moe_up_kernel_timing_enable was not called");
+    if (every < 1) return fail(MOE_ERR_INVALID_ARG, "every must be at least 1");
+    g_timer.every = every;
+    g_timer.seen = 0;
     return MOE_OK;
 }
 
