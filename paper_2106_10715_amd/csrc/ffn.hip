@@ -503,14 +503,18 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
         const int ci = c + (I);                                                                            \
         const char* a_base = reinterpret_cast<const char*>(A) +                                            \
                              static_cast<size_t>(at(min(ci + AD, last))) * (kKC * 2);                      \
+        /* past the last step there is nothing left to prefetch: the loads still issue (the waits count   \
+           them), but all lanes read the same 16 bytes, one cache line instead of a KiB per load */       \
+        const uint32_t a_first_c = ci + AD > last ? 0u : a_first, a_last_c = ci + AD > last ? 0u : a_last; \
         auto issue_a = [&](auto ic) {                                                                      \
             constexpr int mb = decltype(ic)::value;                                                        \
             if constexpr (mb + 1 < MBS)                                                                    \
-                ld_pinned<0>(areg[((I) + AD) % AD].v[mb], a_first, a_base + static_cast<size_t>(mb) * a_stride); \
+                ld_pinned<0>(areg[((I) + AD) % AD].v[mb], a_first_c, a_base + static_cast<size_t>(mb) * a_stride); \
             else                                                                                           \
-                ld_pinned<0>(areg[((I) + AD) % AD].v[mb], a_last, a_base);                                 \
+                ld_pinned<0>(areg[((I) + AD) % AD].v[mb], a_last_c, a_base);                               \
         };                                                                                                 \
-        const uint32_t voff = static_cast<uint32_t>(at(min(ci + AD + 1, last))) * (kKS * 2048) + lane_off; \
+        const uint32_t voff = static_cast<uint32_t>(at(min(ci + AD + 1, last))) * (kKS * 2048) +           \
+                              (ci + AD + 1 > last ? 0u : lane_off);                                        \
         auto issue_b = [&](auto ic) {                                                                      \
             constexpr int i = decltype(ic)::value, ks = i / NF, j = i % NF;                                \
             ld_pinned_stream<(ks & 1) * 2048 + j * 1024, KEEP>(ring[((I) + AD + 1) % R].v[ks][j],          \
