@@ -132,6 +132,59 @@ def check_loads_in_flight(asm: str, kernel_pattern: str, what: str = "assembly")
     return checked
 
 
+def check_prologue_in_flight(asm: str, kernel_pattern: str, what: str = "assembly") -> int:
+    """The same rule for the code that leads up to each pipelined loop (from "; pipeline begin" to the loop's
+    first block, in layout order, across block labels): the loads written as inline assembly are in flight from
+    their issue until a "s_waitcnt vmcnt(N)" that leaves at most N younger ones outstanding, and nothing may
+    touch their registers before.  Vector memory operations the compiler generated itself in that stretch
+    (one wave takes the block's next work item there) are not put on the list: a wave that does not execute
+    them has fewer operations outstanding, so counting them would retire hand-issued loads too early.
+    Returns the number of stretches checked."""
+    lines = asm.splitlines()
+    kernel, checked, n = None, 0, 0
+    while n < len(lines):
+        line = lines[n]
+        if line.startswith("_Z") and ":" in line:
+            name = line.split(":")[0]
+            kernel = name if kernel_pattern in name else None
+        elif line.strip().startswith(".end_amdhsa_kernel"):
+            kernel = None
+        if kernel is not None and "; pipeline begin" in line:
+            pending, in_asm, m = [], True, n + 1          # the marker itself is inline assembly
+            while m < len(lines):
+                raw = lines[m]
+                t = raw.strip()
+                if "; pipeline end" in t:
+                    break
+                if raw.startswith(".LBB") and "Depth=2" in (raw + (lines[m + 1] if m + 1 < len(lines) else "")):
+                    break
+                if "#ASMSTART" in t:
+                    in_asm = True
+                elif "#ASMEND" in t:
+                    in_asm = False
+                if t and not t.startswith(";") and not raw.startswith("."):
+                    code = t.split(";")[0].strip()
+                    op = code.split()[0]
+                    if op == "s_waitcnt":
+                        got = re.search(r"vmcnt\((\d+)\)", code)
+                        if got:
+                            keep = int(got.group(1))
+                            pending = pending[len(pending) - keep:] if 0 < keep < len(pending) else ([] if keep == 0 else pending)
+                    else:
+                        used = _vregs(code)
+                        for regs, at in pending:
+                            if used & regs:
+                                raise RuntimeError(f"{what}: {kernel}: line {m + 1} ({code}) touches v{min(used & regs)}, whose "
+                                                   f"load (line {at}) has not been waited for")
+                        if in_asm and op.startswith(("global_load", "buffer_load", "flat_load")):
+                            pending.append((_vregs(code.split(",")[0]), m + 1))
+                m += 1
+            checked += 1
+            n = m
+        n += 1
+    return checked
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(HERE, "_build", src.replace(".hip", ".o"))
     cmd = [_hipcc(), *FLAGS, *EXTRA.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
@@ -145,7 +198,7 @@ def _compile(src: str) -> str:
             raise RuntimeError(f"hipcc -S failed on {src}:\n{ra.stderr}")
         text = open(asm).read()
         check_no_spill(text, NO_SPILL[src], src)
-        if check_loads_in_flight(text, NO_SPILL[src], src) == 0:
+        if check_loads_in_flight(text, NO_SPILL[src], src) == 0 or check_prologue_in_flight(text, NO_SPILL[src], src) == 0:
             raise RuntimeError(f"{src}: no pipelined loop found to verify (markers missing?)")
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
     if r.returncode != 0:

@@ -162,6 +162,33 @@ def test_build_refuses_a_loop_that_touches_a_register_with_a_load_in_flight():
         check_loads_in_flight(kernel(good[:2] + [".LBB0_3:"] + good[2:]).replace("\t.LBB0_3:", ".LBB0_3:"), "ffn_mfma")
 
 
+def test_build_refuses_a_touch_of_a_register_in_flight_before_the_loop():
+    """The third assembly check covers the code between the start of a pipeline region and its loop: loads
+    issued as inline assembly are in flight until a wait retires them; loads the compiler generated are
+    not counted (a wave that does not execute them would otherwise look further along than it is)."""
+    from paper_2106_10715_amd.build import check_prologue_in_flight
+
+    def kernel(body):
+        return "\n".join(["_ZN3moe8ffn_mfma_kernelEv: ; @x", "\t;;#ASMSTART", "\t; pipeline begin", "\t;;#ASMEND"]
+                         + ["\t" + l for l in body] +
+                         [".LBB0_2:                                ;   Parent Loop BB0_1 Depth=1",
+                          "                                        ; =>  This Inner Loop Header: Depth=2",
+                          "\ts_cbranch_scc1 .LBB0_2", "\t; pipeline end", "\t.end_amdhsa_kernel"])
+
+    asm_load = lambda dst, off: [";;#ASMSTART", f"global_load_dwordx4 {dst}, v40, s[2:3] offset:{off}", ";;#ASMEND"]
+    good = (asm_load("v[4:7]", 0) + asm_load("v[8:11]", 1024) + ["s_waitcnt vmcnt(1)", "ds_write_b128 v50, v[4:7]"])
+    assert check_prologue_in_flight(kernel(good), "ffn_mfma") == 1
+    with pytest.raises(RuntimeError, match="has not been waited for"):
+        check_prologue_in_flight(kernel(good + ["v_mov_b32_e32 v60, v9"]), "ffn_mfma")
+    # a load of the compiler's own between the two does not make the wait look stricter than it is:
+    # counted, vmcnt(2) would seem to retire v[4:7]; for a wave that skips the branch it does not
+    own = (asm_load("v[4:7]", 0) + asm_load("v[8:11]", 1024) + [".LBB0_1:", "global_load_dword v70, v71, s[4:5]",
+           "s_waitcnt vmcnt(2)", "ds_write_b128 v50, v[4:7]"])
+    with pytest.raises(RuntimeError, match="has not been waited for"):
+        check_prologue_in_flight(kernel(own).replace("\t.LBB0_1:", ".LBB0_1:"), "ffn_mfma")
+    assert check_prologue_in_flight(kernel(good).replace("ffn_mfma", "other"), "ffn_mfma") == 0
+
+
 def test_gelu_tail_polynomial_of_the_ffn_kernel_is_accurate():
     """The bf16 FFN epilogue evaluates exact GELU as max(z, 0) - a 2^P(a), a = min(|z|, 8), with the seven
     coefficients of P written in ffn.hip.  Evaluated here in float32 steps like the kernel's fused
