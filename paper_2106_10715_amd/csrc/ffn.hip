@@ -605,16 +605,33 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
         const int out_unit = unit - wave + src_wave;            // unit of the wave that produced them
         if (out_unit < N / W) {
             uint16_t* cbase = C + static_cast<size_t>(out_unit) * W + (seg % W);
-            for (int r = tid / kLanesPerRow; r < kRowsPerPass && p0 + r < rows; r += kRowsPerIter) {
-                const uint4 val = *reinterpret_cast<const uint4*>(tile + r * kTileRowBytes + seg * 2);
-                // row_map: where each row of the batched order goes (the layer's output rows, when the rows
-                // need no weighting afterwards); none: the batched order itself
-                const int out_row = row_map != nullptr ? row_map[row_begin + p0 + r] : row_begin + p0 + r;
-                // written once and next read by another kernel, after far more traffic than the L2 holds: stored
-                // non-temporal, so that the rows do not take the place of weights and activation tiles there
-                // (5 % of the layer's time at 128 tokens per expert)
-                __builtin_nontemporal_store(u32x4{val.x, val.y, val.z, val.w},
-                                            reinterpret_cast<u32x4*>(cbase + static_cast<size_t>(out_row) * N));
+            // All pieces of the pass are read from the tile (and their output rows looked up) before the first
+            // is stored: one LDS and one look-up latency per pass instead of one per piece.
+            //   row_map: where each row of the batched order goes (the layer's output rows, when the rows
+            //   need no weighting afterwards); none: the batched order itself
+            constexpr int kPieces = kRowsPerPass / kRowsPerIter;
+            uint4 val[kPieces];
+            int out_row[kPieces];
+#pragma unroll
+            for (int i = 0; i < kPieces; ++i) {
+                if (i * kRowsPerIter < MBS * 32 - p0) {                   // rows this tile height has
+                    const int r = static_cast<int>(tid) / kLanesPerRow + i * kRowsPerIter;
+                    val[i] = *reinterpret_cast<const uint4*>(tile + r * kTileRowBytes + seg * 2);
+                    const int row = row_begin + min(p0 + r, rows - 1);    // past the end: the last row again, not stored
+                    out_row[i] = row_map != nullptr ? row_map[row] : row;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < kPieces; ++i) {
+                if (i * kRowsPerIter < MBS * 32 - p0) {
+                    const int r = static_cast<int>(tid) / kLanesPerRow + i * kRowsPerIter;
+                    // written once and next read by another kernel, after far more traffic than the L2 holds: stored
+                    // non-temporal, so that the rows do not take the place of weights and activation tiles there
+                    // (5 % of the layer's time at 128 tokens per expert)
+                    if (p0 + r < rows)
+                        __builtin_nontemporal_store(u32x4{val[i].x, val[i].y, val[i].z, val[i].w},
+                                                    reinterpret_cast<u32x4*>(cbase + static_cast<size_t>(out_row[i]) * N));
+                }
             }
         }
     }
