@@ -379,7 +379,11 @@ constexpr int gate_parts() { return NB <= 4 ? kGateWaves : 1; }      // one part
 template <int NB>
 constexpr size_t gate_tile_bytes() { return static_cast<size_t>(gate_parts<NB>()) * kGateTokens * (NB * 32 + 1) * sizeof(float); }
 
-template <int NB>
+// TOK: tokens a block really has (32, 16 or 8).  The MFMA tile always has 32 token rows; with fewer tokens
+// the rows repeat them (the same addresses, so no more bytes are read) and only the first TOK are ranked.
+// A short batch gets more, smaller blocks this way: a block's time is mostly its own loads through one
+// compute unit plus a selection that is a latency chain per token, and 128 blocks leave half the chip idle.
+template <int NB, int TOK>
 __global__ __launch_bounds__(kGateWaves * 64) void route_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wg,
                                                          const uint4* __restrict__ pack, const float* __restrict__ part,
                                                          const float* __restrict__ bias, int32_t* __restrict__ idx,
@@ -396,7 +400,7 @@ __global__ __launch_bounds__(kGateWaves * 64) void route_mfma_kernel(const uint1
     auto tile_at = [&](int p, int tok, int e) -> float& { return part_tile[(p * kGateTokens + tok) * (EP + 1) + e]; };
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int t0 = blockIdx.x * kGateTokens;
+    const int t0 = blockIdx.x * TOK;
     const int nS = d / 64;
 
     // A wave's groups S = wave, wave + 8, ... are taken kAhead at a time: the token pieces of all of them are
@@ -406,7 +410,7 @@ __global__ __launch_bounds__(kGateWaves * 64) void route_mfma_kernel(const uint1
     // per SIMD hold for this number of expert blocks).
     constexpr int kAhead = NB <= 2 ? 4 : NB <= 4 ? 2 : 1;
     constexpr int kRing = NB <= 1 ? 3 : 2;
-    const int row = min(t0 + (lane & 31), T - 1);
+    const int row = min(t0 + (lane & (TOK - 1)), T - 1);
     const uint4* xrow = reinterpret_cast<const uint4*>(x + static_cast<size_t>(row) * d + 32 * (lane >> 5));
     uint4 xv[kAhead][4];
     auto fetch_x = [&](int S0) {
@@ -530,7 +534,7 @@ __global__ __launch_bounds__(kGateWaves * 64) void route_mfma_kernel(const uint1
 #pragma unroll
     for (int i = 0; i < kNE; ++i) bl[i] = i >= NE ? 0.f : (bias != nullptr && eg + 64 * i < E) ? bias[eg + 64 * i] : 0.f;
     const double wn2 = static_cast<double>(wn2_sh);
-    for (int tt = wave; tt < kGateTokens; tt += kGateWaves) {
+    for (int tt = wave; tt < TOK; tt += kGateWaves) {
         const int t = t0 + tt;
         if (t >= T) { if (lane == 0) flagged[tt] = 0; continue; }
         // this lane's logits, fp32 (a -0 becomes +0: equal logits must compare equal) and as ordered keys
@@ -652,7 +656,7 @@ __global__ __launch_bounds__(kGateWaves * 64) void route_mfma_kernel(const uint1
     // same packed fragments and with the same split as the MFMA pass: wave w takes the groups
     // S = w, w+8, ..., lane (c, h) the 32 rows 64 S + 32 h .. of column c of every expert block; the two
     // halves are added by a lane exchange, the waves in wave order.
-    unsigned long long todo = __ballot(lane < kGateTokens && flagged[lane & (kGateTokens - 1)] != 0);   // the same in every wave
+    unsigned long long todo = __ballot(lane < TOK && flagged[lane & (TOK - 1)] != 0);   // the same in every wave
     while (todo != 0ull) {
         const int tt = __ffsll(static_cast<long long>(todo)) - 1;
         todo &= todo - 1ull;
@@ -744,26 +748,34 @@ int launch_route(const moe_cfg& c, const void* x, const void* Wg, const float* b
         hipLaunchKernelGGL(gate_prep_kernel, dim3(c.d / 64), dim3(256), 0, s, static_cast<const uint16_t*>(Wg), c.d, cols, NB,
                            pack, part);
         MOE_LAUNCH_CHECK("gate_prep_kernel");
-        dim3 grid((c.T + kGateTokens - 1) / kGateTokens), block(kGateWaves * 64);
-        int dev = 0;
+        int dev = 0, n_cu = 0;
         MOE_HIP_CHECK(hipGetDevice(&dev));
-#define MOE_ROUTE_CASE(N)                                                                                             \
-    case N:                                                                                                           \
+        if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0) n_cu = 256;
+        // as many tokens per block as still give every compute unit a block
+        const int tok = (c.T + 31) / 32 >= n_cu ? 32 : (c.T + 15) / 16 >= n_cu ? 16 : 8;
+        dim3 grid((c.T + tok - 1) / tok), block(kGateWaves * 64);
+#define MOE_ROUTE_LAUNCH(N, TK)                                                                                       \
+    {                                                                                                                 \
         if (static int raised_on = -1; raised_on != dev) {     /* the tiles of 64 experts and more exceed the default */ \
-            MOE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&route_mfma_kernel<N>),                   \
+            MOE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&route_mfma_kernel<N, TK>),               \
                                               hipFuncAttributeMaxDynamicSharedMemorySize,                             \
                                               static_cast<int>(gate_tile_bytes<N>())));                               \
             raised_on = dev;                                                                                          \
         }                                                                                                             \
-        hipLaunchKernelGGL(route_mfma_kernel<N>, grid, block, gate_tile_bytes<N>(), s, static_cast<const uint16_t*>(x), \
-                           static_cast<const uint16_t*>(Wg), pack, part, bias, idx, w, c.T, c.d, cols, c.k, c.renorm, \
-                           hash);                                                                                     \
+        hipLaunchKernelGGL((route_mfma_kernel<N, TK>), grid, block, gate_tile_bytes<N>(), s,                          \
+                           static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(Wg), pack, part, bias, idx,  \
+                           w, c.T, c.d, cols, c.k, c.renorm, hash);                                                   \
+    }
+#define MOE_ROUTE_CASE(N)                                                                                             \
+    case N:                                                                                                           \
+        if (tok == 32) MOE_ROUTE_LAUNCH(N, 32) else if (tok == 16) MOE_ROUTE_LAUNCH(N, 16) else MOE_ROUTE_LAUNCH(N, 8) \
         break;
         switch (NB) {
             MOE_ROUTE_CASE(1) MOE_ROUTE_CASE(2) MOE_ROUTE_CASE(3) MOE_ROUTE_CASE(4)
             MOE_ROUTE_CASE(5) MOE_ROUTE_CASE(6) MOE_ROUTE_CASE(7) MOE_ROUTE_CASE(8)
             default: return fail(MOE_ERR_UNSUPPORTED, "E = %d is out of range", c.E);
         }
+#undef MOE_ROUTE_LAUNCH
 #undef MOE_ROUTE_CASE
         MOE_LAUNCH_CHECK("route_mfma_kernel");
         return MOE_OK;
