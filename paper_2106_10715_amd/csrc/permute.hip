@@ -101,6 +101,80 @@ __global__ __launch_bounds__(256) void scatter_kernel(const int32_t* __restrict_
     }
 }
 
+// Short batches: the same three steps by one block of 16 waves, with no trip through memory between them:
+// LDS histogram of all assignments, exclusive scan over the experts, then the stable scatter in rounds
+// of 1024 assignments (rank inside the wave from ballots, waves in order, rounds in order).
+constexpr int kSmallWaves = 16;
+constexpr int kSmallMaxA = 16 * kSmallWaves * 64;      // beyond this the chunked kernels spread the work over the chip
+
+__global__ __launch_bounds__(kSmallWaves * 64) void permute_small_kernel(const int32_t* __restrict__ idx, int A, int E,
+                                                                         int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
+                                                                         int32_t* __restrict__ perm, int32_t* __restrict__ inv) {
+    __shared__ int run[256];                       // histogram, then the next free row of each expert
+    __shared__ int wcnt[kSmallWaves][256];         // per wave, rows each expert takes in the current round
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x < 256) {
+        run[threadIdx.x] = 0;
+#pragma unroll
+        for (int wv = 0; wv < kSmallWaves; ++wv) wcnt[wv][threadIdx.x] = 0;
+    }
+    __syncthreads();
+    for (int a = threadIdx.x; a < A; a += kSmallWaves * 64) atomicAdd(&run[clamp_expert(idx[a], E)], 1);   // integer counts: order cannot matter
+    __syncthreads();
+    if (wave == 0) {
+        // exclusive scan of up to 256 counts by one wave: four experts per lane, then across the lanes
+        int c[4], sum = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { c[j] = run[4 * lane + j]; sum += c[j]; }
+        int incl = sum;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        int start = incl - sum;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int e = 4 * lane + j;
+            if (e < E) { counts[e] = c[j]; offsets[e] = start; }
+            run[e] = start;
+            start += c[j];
+        }
+        if (lane == 63) offsets[E] = incl;         // experts past E hold no assignment, so this is the total
+    }
+    __syncthreads();
+    int bits = 0;
+    while ((1 << bits) < E) ++bits;
+    for (int a0 = 0; a0 < A; a0 += kSmallWaves * 64) {
+        const int a = a0 + threadIdx.x;
+        const bool valid = a < A;
+        const int e = valid ? clamp_expert(idx[a], E) : 0;
+        unsigned long long peers = __ballot(valid);       // lanes of this wave that hold the same expert
+        for (int b = 0; b < bits; ++b) {
+            const bool bit = (e >> b) & 1;
+            const unsigned long long bal = __ballot(bit);
+            peers &= bit ? bal : ~bal;
+        }
+        const int rank = __popcll(peers & ((1ull << lane) - 1ull));
+        if (valid && rank == 0) wcnt[wave][e] = __popcll(peers);
+        __syncthreads();
+        if (valid) {
+            int row = run[e] + rank;
+            for (int wv = 0; wv < wave; ++wv) row += wcnt[wv][e];
+            perm[row] = a;
+            inv[a] = row;
+        }
+        __syncthreads();
+        if (threadIdx.x < 256) {
+            int taken = 0;
+#pragma unroll
+            for (int wv = 0; wv < kSmallWaves; ++wv) { taken += wcnt[wv][threadIdx.x]; wcnt[wv][threadIdx.x] = 0; }
+            run[threadIdx.x] += taken;
+        }
+        __syncthreads();
+    }
+}
+
 // One block per destination row; 16-byte vectors, coalesced on both sides.
 __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ perm,
                                                           int k, int vec_per_row, uint4* __restrict__ Xp) {
@@ -123,15 +197,18 @@ int launch_permute(const moe_cfg& c, const void* x, const int32_t* idx, int32_t*
                    int32_t* perm, int32_t* inv, void* Xp, int32_t* chunk_hist, hipStream_t s) {
     const int A = c.T * c.k;
     const int chunks = (A + kPermChunk - 1) / kPermChunk;
-    if (chunks > 0) {
+    if (A <= kSmallMaxA) {
+        hipLaunchKernelGGL(permute_small_kernel, dim3(1), dim3(kSmallWaves * 64), 0, s, idx, A, c.E, counts, offsets, perm, inv);
+        MOE_LAUNCH_CHECK("permute_small_kernel");
+    } else {
         hipLaunchKernelGGL(chunk_hist_kernel, dim3(chunks), dim3(256), 0, s, idx, A, c.E, chunk_hist);
         MOE_LAUNCH_CHECK("chunk_hist_kernel");
-    }
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), 0, s, chunk_hist, chunks, c.E, counts, offsets);
-    MOE_LAUNCH_CHECK("scan_kernel");
-    if (chunks > 0) {
+        hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), 0, s, chunk_hist, chunks, c.E, counts, offsets);
+        MOE_LAUNCH_CHECK("scan_kernel");
         hipLaunchKernelGGL(scatter_kernel, dim3(chunks), dim3(256), 0, s, idx, A, c.E, chunk_hist, perm, inv);
         MOE_LAUNCH_CHECK("scatter_kernel");
+    }
+    if (chunks > 0) {
         if (Xp != nullptr) {
             const int vec_per_row = static_cast<int>(c.d * elem_size(c) / 16);
             hipLaunchKernelGGL(gather_rows_kernel, dim3(A), dim3(256), 0, s, static_cast<const uint4*>(x), perm, c.k,
