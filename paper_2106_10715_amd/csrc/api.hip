@@ -235,15 +235,18 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
     if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[0], s));
     if (int rc = launch_route(c, x, W_g, gate_bias, idx, w, base + L.route, s)) return rc;
     if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[1], s));
+    bool planned = false;          // resident mode: the work list of the one FFN launch may come from the batching kernel
     if (int rc = launch_permute(c, x, idx, counts, offsets, perm, inv, base + L.Xp,
-                                reinterpret_cast<int32_t*>(base + L.chunk_hist), s))
+                                reinterpret_cast<int32_t*>(base + L.chunk_hist), s,
+                                sctx == nullptr ? reinterpret_cast<int32_t*>(base + L.ffn_plan) : nullptr,
+                                static_cast<int>(ffn_plan_tiles(c)), sctx == nullptr ? &planned : nullptr))
         return rc;
     if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[2], s));
 
     if (sctx == nullptr) {
         if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, 0, c.E, W_packed, eb, A, base + L.H, ffn_out,
                                        reinterpret_cast<int32_t*>(base + L.ffn_plan), s, tev ? tev[3] : nullptr,
-                                       tev && g_timer.up_only ? tev[2] : nullptr, row_map))
+                                       tev && g_timer.up_only ? tev[2] : nullptr, row_map, planned))
             return rc;
         if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[4], s));
     } else {

@@ -64,7 +64,11 @@ int gate_columns(const moe_cfg& c);
 int launch_route(const moe_cfg& c, const void* x, const void* Wg, const float* bias, int32_t* idx, float* w,
                  void* scratch, hipStream_t s);
 int launch_permute(const moe_cfg& c, const void* x, const int32_t* idx, int32_t* counts, int32_t* offsets,
-                   int32_t* perm, int32_t* inv, void* Xp, int32_t* chunk_hist, hipStream_t s);
+                   int32_t* perm, int32_t* inv, void* Xp, int32_t* chunk_hist, hipStream_t s, int32_t* plan = nullptr,
+                   int plan_max_tiles = 0, bool* planned = nullptr);
+// plan/planned: for short bf16 batches the kernel that batches the tokens also writes the work list of the expert
+// FFN launch over all experts that follows (room for plan_max_tiles row tiles) and sets *planned; the caller then
+// passes plan_ready to launch_expert_ffn.
 int launch_pack(const moe_cfg& c, const void* Win, const void* Wgate, const void* Wout, void* packed, hipStream_t s);
 // Runs the FFN of experts [e_first, e_first + e_count); W points at the packed block of e_first and
 // consecutive experts are expert_stride_bytes apart.  max_rows bounds the rows those experts can hold
@@ -74,7 +78,7 @@ int launch_pack(const moe_cfg& c, const void* Win, const void* Wgate, const void
 int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, int e_first, int e_count,
                       const void* W, size_t expert_stride_bytes, long max_rows, void* H, void* Yp, int32_t* plan,
                       hipStream_t s, hipEvent_t between = nullptr, hipEvent_t before_up = nullptr,
-                      const int32_t* row_map = nullptr);
+                      const int32_t* row_map = nullptr, bool plan_ready = false);
 // row_map (bf16 only): row r of the batched order is written to row row_map[r] of Yp instead of row r, which
 // turns the down-projection's output into the layer's output when no weighting follows (see moe_layer_forward).
 // `plan`: ffn_plan_bytes(c) bytes of workspace, rewritten by every launch_expert_ffn (room for ffn_plan_tiles(c) row tiles).

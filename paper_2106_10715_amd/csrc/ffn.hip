@@ -13,6 +13,7 @@
 // weights once from HBM, which is what this layout is built for.
 // fp32 path: plain LDS-tiled FMA kernel (small-shape correctness vehicle).
 #include "common.h"
+#include "ffn_plan.h"
 
 #include <type_traits>
 
@@ -637,52 +638,13 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
     }
 }
 
-// Work list of one launch: which (expert, rows) every row tile covers, in the order the tiles are
-// handed out.  Experts with more rows come first, so that the tiles that finish last are the short
-// ones; an expert's rows are split evenly over its tiles (in multiples of 32 rows), not into full
-// tiles and a small remainder.  Also clears the work counters of the two kernels that follow.
-//   plan[0..7], plan[8..15] : next work item of each of the 8 queues, up and down kernel
-//   plan[16]                : number of tiles
-//   plan[32 + 4 s ..]       : tile s = (expert, first row, rows, row tiles of this expert)
-constexpr int kPlanHeader = 32;
+// The work list of a launch is written by ffn_plan_block (ffn_plan.h): here as a kernel of its own.
 constexpr int kKeepFromTiles = 2;       // row tiles of an expert from which its weights are worth keeping in the L2
 
 __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict__ offsets, int e_first, int e_count,
                                                        int tile_m, int32_t* __restrict__ plan, int total_rows, int max_tiles) {
-    __shared__ int n[256], first[256], order[256], tl[256];
-    const int t = threadIdx.x;
-    int cnt = 0, lo = 0;
-    if (t < e_count) {
-        // whatever the offsets hold, no tile may reach outside the total_rows rows or the work list
-        lo = min(max(offsets[e_first + t], 0), total_rows);
-        cnt = min(max(offsets[e_first + t + 1] - lo, 0), total_rows - lo);
-    }
-    n[t] = cnt;
-    first[t] = lo;
-    order[t] = t;
-    tl[t] = 0;
-    __syncthreads();
-    if (t < e_count) {
-        int rank = 0;                   // more rows first, equal counts by expert index: a permutation of 0..e_count-1
-        for (int u = 0; u < e_count; ++u) rank += (n[u] > cnt || (n[u] == cnt && u < t)) ? 1 : 0;
-        order[rank] = t;
-    }
-    __syncthreads();
-    const int mine = order[t], my_n = t < e_count ? n[mine] : 0;
-    const int my_tiles = (my_n + tile_m - 1) / tile_m;
-    tl[t] = my_tiles;
-    __syncthreads();
-    int start = 0;
-    const int upto = t < e_count ? t : e_count;
-    for (int r = 0; r < upto; ++r) start += tl[r];
-    if (my_tiles > 0) {
-        const int per_tile = min(tile_m, ((my_n + my_tiles - 1) / my_tiles + 31) & ~31);
-        int4* tiles = reinterpret_cast<int4*>(plan + kPlanHeader);
-        for (int mt = 0; mt < my_tiles && start + mt < max_tiles; ++mt)
-            tiles[start + mt] = make_int4(e_first + mine, first[mine] + mt * per_tile, min(per_tile, my_n - mt * per_tile), my_tiles);
-    }
-    if (t == 255) plan[16] = min(start + my_tiles, max_tiles);
-    if (t < 16) plan[t] = 0;
+    __shared__ int scratch[4][256];
+    ffn_plan_block(offsets, e_first, e_count, tile_m, plan, total_rows, max_tiles, scratch);
 }
 
 // C[rows of one expert tile, N] = A[rows, K] * B_e, B_e in packed fragment order.
@@ -893,7 +855,7 @@ int launch_pack(const moe_cfg& c, const void* Win, const void* Wgate, const void
 
 int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, int e_first, int e_count,
                       const void* W, size_t expert_stride_bytes, long max_rows, void* H, void* Yp, int32_t* plan,
-                      hipStream_t s, hipEvent_t between, hipEvent_t before_up, const int32_t* row_map) {
+                      hipStream_t s, hipEvent_t between, hipEvent_t before_up, const int32_t* row_map, bool plan_ready) {
     if (max_rows <= 0 || e_count <= 0) return MOE_OK;
     const size_t df = static_cast<size_t>(c.d) * c.f;
     if (c.dtype == MOE_BF16) {
@@ -915,9 +877,11 @@ int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, 
             return n;
         }();
         auto grid_for = [&](long items) { return dim3(static_cast<unsigned>(items < n_cu ? items : n_cu)); };
-        hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, s, offsets, e_first, e_count, kTileM, plan,
-                           c.T * c.k, static_cast<int>(ffn_plan_tiles(c)));
-        MOE_LAUNCH_CHECK("ffn_plan_kernel");
+        if (!plan_ready) {          // else the kernel that batched the tokens has written the work list as well
+            hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, s, offsets, e_first, e_count, kTileM, plan,
+                               c.T * c.k, static_cast<int>(ffn_plan_tiles(c)));
+            MOE_LAUNCH_CHECK("ffn_plan_kernel");
+        }
         if (before_up != nullptr) MOE_HIP_CHECK(hipEventRecord(before_up, s));
         const size_t down_off = 2 * df * 2;
         dim3 block(256);

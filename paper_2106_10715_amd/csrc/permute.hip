@@ -7,6 +7,7 @@
 //   3. scatter_kernel    : stable rank inside the chunk from wave ballots (no ordered atomics)
 //   4. gather_rows_kernel: 16-byte-vector row copy
 #include "common.h"
+#include "ffn_plan.h"
 
 namespace moe {
 namespace {
@@ -109,7 +110,8 @@ constexpr int kSmallMaxA = 16 * kSmallWaves * 64;      // beyond this the chunke
 
 __global__ __launch_bounds__(kSmallWaves * 64) void permute_small_kernel(const int32_t* __restrict__ idx, int A, int E,
                                                                          int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
-                                                                         int32_t* __restrict__ perm, int32_t* __restrict__ inv) {
+                                                                         int32_t* __restrict__ perm, int32_t* __restrict__ inv,
+                                                                         int32_t* __restrict__ plan, int plan_max_tiles) {
     __shared__ int run[256];                       // histogram, then the next free row of each expert
     __shared__ int wcnt[kSmallWaves][256];         // per wave, rows each expert takes in the current round
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -143,6 +145,17 @@ __global__ __launch_bounds__(kSmallWaves * 64) void permute_small_kernel(const i
         if (lane == 63) offsets[E] = incl;         // experts past E hold no assignment, so this is the total
     }
     __syncthreads();
+    // the work list of the expert kernels that follow, when the caller wants it from here (saves a launch)
+    if (plan != nullptr) {
+        int (&scratch)[4][256] = reinterpret_cast<int (&)[4][256]>(wcnt);      // not in use yet; cleared again below
+        ffn_plan_block(offsets, 0, E, kTileM, plan, A, plan_max_tiles, scratch);
+        __syncthreads();
+        if (threadIdx.x < 256) {
+#pragma unroll
+            for (int wv = 0; wv < 4; ++wv) wcnt[wv][threadIdx.x] = 0;
+        }
+        __syncthreads();
+    }
     int bits = 0;
     while ((1 << bits) < E) ++bits;
     for (int a0 = 0; a0 < A; a0 += kSmallWaves * 64) {
@@ -194,12 +207,17 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restric
 }  // namespace
 
 int launch_permute(const moe_cfg& c, const void* x, const int32_t* idx, int32_t* counts, int32_t* offsets,
-                   int32_t* perm, int32_t* inv, void* Xp, int32_t* chunk_hist, hipStream_t s) {
+                   int32_t* perm, int32_t* inv, void* Xp, int32_t* chunk_hist, hipStream_t s, int32_t* plan,
+                   int plan_max_tiles, bool* planned) {
+    if (planned != nullptr) *planned = false;
     const int A = c.T * c.k;
     const int chunks = (A + kPermChunk - 1) / kPermChunk;
     if (A <= kSmallMaxA) {
-        hipLaunchKernelGGL(permute_small_kernel, dim3(1), dim3(kSmallWaves * 64), 0, s, idx, A, c.E, counts, offsets, perm, inv);
+        const bool with_plan = plan != nullptr && planned != nullptr && c.dtype == MOE_BF16 && A > 0;
+        hipLaunchKernelGGL(permute_small_kernel, dim3(1), dim3(kSmallWaves * 64), 0, s, idx, A, c.E, counts, offsets, perm, inv,
+                           with_plan ? plan : nullptr, plan_max_tiles);
         MOE_LAUNCH_CHECK("permute_small_kernel");
+        if (with_plan) *planned = true;
     } else {
         hipLaunchKernelGGL(chunk_hist_kernel, dim3(chunks), dim3(256), 0, s, idx, A, c.E, chunk_hist);
         MOE_LAUNCH_CHECK("chunk_hist_kernel");
