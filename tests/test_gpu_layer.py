@@ -265,3 +265,34 @@ def test_resident_layer_can_be_captured_in_a_graph_and_replayed():
             assert torch.equal(L.y, y_eager), f"replay {rep}"
         scratch = torch.randn(1 << 16, device="cuda").sum().item()           # unrelated eager work between replays
         assert scratch == scratch
+
+
+def test_stage_and_up_kernel_timers_count_the_calls_they_should():
+    """The measurement aids of the library: per-stage events for up to N resident calls, or two events around the
+    up-projection kernel of every `every`-th resident call; neither changes the result."""
+    wl = W.Workload("timers", T=300, d=256, f=384, E=4, k=1, dtype="bf16", seed=95)
+    L = H.build_layer(wl)
+    M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)
+    torch.cuda.synchronize()
+    y_plain = L.y.clone()
+    M.moe_stage_timing_enable(3)
+    for _ in range(5):                                       # only the first three calls have room
+        M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)
+    torch.cuda.synchronize()
+    per_call = M.moe_stage_timing_read(8)
+    assert len(per_call) == 3
+    assert all(set(c) == set(M.STAGES) and all(v >= 0.0 for v in c.values()) for c in per_call)
+    assert all(c["ffn_up"] > 0.0 and c["ffn_down"] > 0.0 for c in per_call)
+    assert torch.equal(L.y, y_plain)
+    M.moe_up_kernel_timing_enable(4, 2)                      # replaces the stage timer: calls 0, 2, 4, 6
+    for _ in range(7):
+        M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)
+    torch.cuda.synchronize()
+    ups = M.moe_up_kernel_timing_read(8)
+    assert len(ups) == 4 and all(0.0 < u < 50.0 for u in ups)
+    assert torch.equal(L.y, y_plain)
+    with pytest.raises(M.MoeError):
+        M.moe_stage_timing_read(8)                           # the wrong reader for this timer
+    M.moe_stage_timing_disable()
+    with pytest.raises(M.MoeError):
+        M.moe_up_kernel_timing_enable(0)                     # room for at least one call is required
