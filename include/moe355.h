@@ -143,6 +143,8 @@ int moe_combine(const moe_cfg* cfg, const void* Yp, const int32_t* inv, const fl
  *   and compute-before-slot-reuse.  Experts without tokens are not loaded.  Every call reloads every
  *   non-empty expert.  The call returns with the remaining work enqueued on `stream`.
  *   Results are bitwise identical in both modes.
+ *   Resident calls consist of kernel launches only and can be recorded into a HIP graph; with more than 32
+ *   experts, run one call outside the capture first (the gate kernel raises its LDS limit once per device).
  */
 int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const float* gate_bias,
                       const void* W_packed, moe_stream_ctx* sctx, void* y, void* ws, void* stream);

@@ -756,7 +756,8 @@ int launch_route(const moe_cfg& c, const void* x, const void* Wg, const float* b
         dim3 grid((c.T + tok - 1) / tok), block(kGateWaves * 64);
 #define MOE_ROUTE_LAUNCH(N, TK)                                                                                       \
     {                                                                                                                 \
-        if (static int raised_on = -1; raised_on != dev) {     /* the tiles of 64 experts and more exceed the default */ \
+        /* the tiles of more than 32 experts exceed the default LDS limit of a launch: raised once per device */    \
+        if (static int raised_on = -1; gate_tile_bytes<N>() > 48 * 1024 && raised_on != dev) {                        \
             MOE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&route_mfma_kernel<N, TK>),               \
                                               hipFuncAttributeMaxDynamicSharedMemorySize,                             \
                                               static_cast<int>(gate_tile_bytes<N>())));                               \
