@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Throughput of the CPM-2-MoE feed-forward layer on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c5|c6|c4a|c4b]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c5|c6|c4a|c4b] [--tokens T]
 
 A step is one moe_layer_forward (route -> permute -> expert FFNs -> combine) over one batch of
 seeded synthetic tokens that is already resident in HBM.  Prints ONE JSON line: whole-layer
@@ -28,8 +28,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak, published
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed steps (default 200 with resident experts, 30 with host-streamed ones)")
+    ap.add_argument("--warmup", type=int, default=None,
+                    help="untimed steps before them (default 30 resident: the first twenty or so steps after an idle "
+                         "GPU run 2-3 %% slower than the steady state; 5 streamed)")
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4a", "c4b", "c5", "c6"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tokens", type=int, default=None,
@@ -143,6 +146,12 @@ def main():
     if args.streamed and not wl.streamed:
         import dataclasses
         wl = dataclasses.replace(wl, streamed=True, name=wl.name + "-streamed")
+    if args.steps is None:
+        args.steps = 30 if wl.streamed else 200
+    if args.warmup is None:
+        args.warmup = 5 if wl.streamed else 30
+    if args.steps < 1 or args.warmup < 0:
+        sys.exit("bench.py: --steps must be positive and --warmup not negative")
     t_setup = time.perf_counter()
     L = H.build_layer(wl, resident=not wl.streamed, host_copy=wl.streamed)
     print(f"[bench] {wl.name}: inputs resident after {time.perf_counter() - t_setup:.1f} s", file=sys.stderr, flush=True)
