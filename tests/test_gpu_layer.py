@@ -79,6 +79,40 @@ def test_layer_forward_resident_matches_oracle(wl):
         assert (p.counts == 0).sum() >= wl.n_dead
 
 
+def _random_layer(seed):
+    rng = np.random.default_rng(7000 + seed)
+    E = int(rng.choice([1, 2, 3, 5, 8, 16, 31, 32, 33, 40]))
+    hashed = seed % 5 == 4 and E in (2, 8, 16, 32)
+    k = 1 if hashed else int(rng.integers(1, min(E, 3) + 1))
+    return W.Workload(f"rnd{seed}", T=int(rng.choice([1, 7, 33, 250, 1023, 1025, 2500])), d=int(rng.choice([64, 128, 256, 320])),
+                      f=int(rng.choice([64, 192, 512])), E=E, k=k, dtype="bf16", seed=7000 + seed,
+                      renorm=int(rng.integers(0, 2)), zipf_s=1.1 if (seed % 3 == 0 and E >= 5 and not hashed) else None,
+                      n_dead=1 if (seed % 3 == 0 and E >= 5 and not hashed) else 0, gate="hash" if hashed else "topk")
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_layer_random_shapes(seed):
+    """Seeded sweep over batch sizes (one token, around the gate's and the batching kernel's block sizes), widths,
+    expert counts, k, both weightings and both gates: integers exact, y within the bar, and the one-call layer
+    bitwise equal to the four steps called one by one."""
+    wl = _random_layer(seed)
+    L = H.build_layer(wl)
+    M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)
+    torch.cuda.synchronize()
+    y_ref, r, p, _ = oracle_layer(wl)
+    s = stagewise(L)
+    what = f"{wl}"
+    assert np.array_equal(s["idx"].cpu().numpy(), r.idx), what
+    assert np.array_equal(s["counts"].cpu().numpy(), p.counts), what
+    assert np.array_equal(s["offsets"].cpu().numpy(), p.offsets), what
+    assert np.array_equal(s["perm"].cpu().numpy(), p.perm), what
+    assert np.array_equal(s["inv"].cpu().numpy(), p.inv), what
+    assert torch.equal(s["y"], L.y), what
+    got = H.to_f64(L.y)
+    assert np.isfinite(got).all(), what
+    assert rel_l2(got, y_ref) <= TOL["bf16"], what
+
+
 def test_identical_experts_give_the_dense_ffn():
     # Section 2.3: the MoE model is initialised with copies of the dense FFN
     wl = W.Workload("dup", T=300, d=128, f=256, E=4, k=2, dtype="bf16", seed=31)
