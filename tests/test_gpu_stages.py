@@ -215,6 +215,9 @@ def gpu_permute(cfg, x, idx_np, dtype, with_rows=True):
     (2048, 64, 256, 4, "bf16", 0.0),
     (5000, 64, 64, 2, "f32", 2.0),           # heavy skew, some experts empty
     (999, 192, 3, 3, "bf16", 0.0),           # k = E
+    (16384, 64, 32, 1, "bf16", 0.0),         # the largest batch one block still sorts alone
+    (16385, 64, 32, 1, "bf16", 0.0),         # one more: per-chunk histograms, scan and scatter kernels
+    (9000, 64, 64, 2, "bf16", 1.5),          # those kernels with several chunks, skew and empty experts
 ])
 def test_permute_matches_oracle(T, d, E, k, dtype, skew):
     rng = np.random.default_rng(T + E)
