@@ -63,6 +63,8 @@ ROUTE_CASES = [
     (19, 320, 8, 8, "f32", 1, True),           # k = E
     (90, 256, 100, 2, "bf16", 0, True),        # four expert blocks: the largest per-wave partial tiles (dynamic LDS)
     (40, 128, 160, 3, "bf16", 1, False),       # five expert blocks: one shared tile, waves add in turn
+    (4100, 128, 32, 1, "bf16", 1, False),      # enough tokens for 16-token gate blocks (shorter batches use 8)
+    (8200, 64, 64, 2, "bf16", 0, True),        # and for full 32-token blocks, ragged last block
 ]
 
 
