@@ -903,10 +903,11 @@ int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, 
         if (between != nullptr) MOE_HIP_CHECK(hipEventRecord(between, s));
         // down-projection: narrow (32-column) units when wide ones would leave compute units idle
         const long tiles_hint = (max_rows + kTileM - 1) / kTileM > e_count ? (max_rows + kTileM - 1) / kTileM : e_count;
-        // (only for low tiles, whose items are bound by their weight stream: on 256-row tiles the narrow unit's
+        // (only while the experts are likely to have a single tile each, mean rows up to 224, and their items are
+        // bound by the weight stream: on 256-row tiles, and once experts spill into second tiles, the narrow unit's
         // second LDS read per MFMA costs more than the idle compute units do; measured on 8 experts: 128 rows per
         // expert 0.148 ms narrow against 0.177 ms wide, 256 rows 0.274 against 0.239)
-        const bool narrow = tiles_hint * ((c.d / 64 + 3) / 4) < 2 * 256 && mean_rows <= 192;
+        const bool narrow = tiles_hint * ((c.d / 64 + 3) / 4) < 2 * 256 && mean_rows <= 224;
         items = items_for(((narrow ? c.d / 32 : c.d / 64) + 3) / 4, yc);
         if (items > 0x7fffffffL) return fail(MOE_ERR_UNSUPPORTED, "too many work items for one launch (%ld)", items);
         if (narrow)
