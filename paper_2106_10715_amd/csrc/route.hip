@@ -384,7 +384,7 @@ constexpr size_t gate_tile_bytes() { return static_cast<size_t>(gate_parts<NB>()
 // A short batch gets more, smaller blocks this way: a block's time is mostly its own loads through one
 // compute unit plus a selection that is a latency chain per token, and 128 blocks leave half the chip idle.
 template <int NB, int TOK>
-__global__ __launch_bounds__(kGateWaves * 64) void route_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wg,
+__global__ __launch_bounds__(kGateWaves * 64, (TOK == 32 && NB == 1) ? 4 : 2) void route_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wg,
                                                          const uint4* __restrict__ pack, const float* __restrict__ part,
                                                          const float* __restrict__ bias, int32_t* __restrict__ idx,
                                                          float* __restrict__ w, int T, int d, int E, int k, int renorm,
@@ -408,8 +408,11 @@ __global__ __launch_bounds__(kGateWaves * 64) void route_mfma_kernel(const uint1
     // requested before the column norms below are worked out), the gate fragments, which every block re-reads
     // from the L2, one or two groups ahead of the MFMAs that use them (as many as the registers of two waves
     // per SIMD hold for this number of expert blocks).
-    constexpr int kAhead = NB <= 2 ? 4 : NB <= 4 ? 2 : 1;
-    constexpr int kRing = NB <= 1 ? 3 : 2;
+    // Long batches (full 32-token blocks, several per compute unit) prefetch less and stay within the registers
+    // of two resident blocks per compute unit, which overlap each other's phases.
+    constexpr bool kTwoBlocks = TOK == 32 && NB == 1;
+    constexpr int kAhead = kTwoBlocks ? 2 : NB <= 2 ? 4 : NB <= 4 ? 2 : 1;
+    constexpr int kRing = (NB <= 1 && !kTwoBlocks) ? 3 : 2;
     const int row = min(t0 + (lane & (TOK - 1)), T - 1);
     const uint4* xrow = reinterpret_cast<const uint4*>(x + static_cast<size_t>(row) * d + 32 * (lane >> 5));
     uint4 xv[kAhead][4];

@@ -65,6 +65,7 @@ ROUTE_CASES = [
     (40, 128, 160, 3, "bf16", 1, False),       # five expert blocks: one shared tile, waves add in turn
     (4100, 128, 32, 1, "bf16", 1, False),      # enough tokens for 16-token gate blocks (shorter batches use 8)
     (8200, 64, 64, 2, "bf16", 0, True),        # and for full 32-token blocks, ragged last block
+    (8200, 128, 32, 1, "bf16", 1, False),      # 32-token blocks of up to 32 experts: two blocks per compute unit
 ]
 
 
