@@ -6,7 +6,7 @@
 A step is one moe_layer_forward (route -> permute -> expert FFNs -> combine) over one batch of
 seeded synthetic tokens that is already resident in HBM.  Prints ONE JSON line: whole-layer
 tokens/s, the roofline figure of the dominant kernel (the fused gate/in up-projection of the expert
-FFNs; duration measured with HIP events on the launch stream inside every third timed step), per-stage
+FFNs; duration measured with HIP events on the launch stream inside every tenth timed step), per-stage
 times, and the CPU oracle timed on the host cores on a bounded sample of the same workload.
 """
 from __future__ import annotations
@@ -181,9 +181,10 @@ def main():
         step()
     torch.cuda.synchronize()
     if not wl.streamed:
-        # two events around the dominant kernel in every third step (each event costs the step some 7 us of
-        # idle time between two kernels)
-        M.moe_up_kernel_timing_enable((args.steps + 2) // 3, 3)
+        # two events around the dominant kernel in every tenth step, every third in short runs (each event costs
+        # the step some 7 us of idle time between two kernels)
+        every = 10 if args.steps >= 100 else 3
+        M.moe_up_kernel_timing_enable((args.steps + every - 1) // every, every)
     copy_ms, copy_bytes, loaded = [], 0, []
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -258,7 +259,7 @@ def main():
             roof = {"bound": "mfma", "achieved": up_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": up_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic}
         roof.update({"kernel": "ffn_mfma_kernel<true> (expert up-projection, gate/in fused)",
-                     "avg_launch_ms": up_ms, "timed_launches": f"{len(up_samples)} of the {args.steps} timed steps (every third)",
+                     "avg_launch_ms": up_ms, "timed_launches": f"{len(up_samples)} of the {args.steps} timed steps (every {every}th)",
                      "algorithmic_bytes_per_launch": up_bytes,
                      "algorithmic_flops_per_launch": 4.0 * d * f * A, "h_staging_bytes_per_launch": A * f * es})
         out["roofline"] = roof
