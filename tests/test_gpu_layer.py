@@ -90,7 +90,7 @@ def _random_layer(seed):
                       n_dead=1 if (seed % 3 == 0 and E >= 5 and not hashed) else 0, gate="hash" if hashed else "topk")
 
 
-@pytest.mark.parametrize("seed", range(20))
+@pytest.mark.parametrize("seed", range(48))
 def test_layer_random_shapes(seed):
     """Seeded sweep over batch sizes (one token, around the gate's and the batching kernel's block sizes), widths,
     expert counts, k, both weightings and both gates: integers exact, y within the bar, and the one-call layer

@@ -386,7 +386,7 @@ def _random_ffn_case(seed):
     return d, f, E, counts
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(56))
 def test_expert_ffn_random_shapes(seed):
     """Seeded sweep over widths, depths and segment lengths (empty, one row, around the 32-row block and the
     256-row tile, several tiles, skewed): every segment on its own against the oracle."""
