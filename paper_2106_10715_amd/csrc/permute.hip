@@ -28,7 +28,10 @@ __global__ __launch_bounds__(256) void chunk_hist_kernel(const int32_t* __restri
     if (threadIdx.x < E) chunk_hist[static_cast<size_t>(blockIdx.x) * E + threadIdx.x] = hist[threadIdx.x];
 }
 
-// One block; thread e walks the chunks of expert e, turning histograms into running bases.
+// One block; thread e walks the chunks of expert e, turning histograms into running bases.  The chunk
+// histograms are read kScanBatch at a time (independent loads: one memory latency per batch, not per chunk).
+constexpr int kScanBatch = 16;
+
 __global__ __launch_bounds__(256) void scan_kernel(int32_t* __restrict__ chunk_hist, int chunks, int E,
                                                    int32_t* __restrict__ counts, int32_t* __restrict__ offsets) {
     __shared__ int total[256];
@@ -36,11 +39,13 @@ __global__ __launch_bounds__(256) void scan_kernel(int32_t* __restrict__ chunk_h
     const int e = threadIdx.x;
     int run = 0;
     if (e < E) {
-        for (int b = 0; b < chunks; ++b) {
-            const size_t at = static_cast<size_t>(b) * E + e;
-            const int h = chunk_hist[at];
-            chunk_hist[at] = run;              // rows of expert e that earlier chunks hold
-            run += h;
+        for (int b0 = 0; b0 < chunks; b0 += kScanBatch) {
+            int h[kScanBatch];
+#pragma unroll
+            for (int i = 0; i < kScanBatch; ++i)
+                h[i] = b0 + i < chunks ? chunk_hist[static_cast<size_t>(b0 + i) * E + e] : 0;
+#pragma unroll
+            for (int i = 0; i < kScanBatch; ++i) run += h[i];
         }
     }
     total[e] = e < E ? run : 0;
@@ -54,7 +59,18 @@ __global__ __launch_bounds__(256) void scan_kernel(int32_t* __restrict__ chunk_h
     if (e < E) {
         counts[e] = total[e];
         offsets[e] = start[e];
-        for (int b = 0; b < chunks; ++b) chunk_hist[static_cast<size_t>(b) * E + e] += start[e];
+        int base = start[e];                   // first row of expert e in the chunk at hand: its rows in earlier chunks come first
+        for (int b0 = 0; b0 < chunks; b0 += kScanBatch) {
+            int h[kScanBatch];
+#pragma unroll
+            for (int i = 0; i < kScanBatch; ++i)
+                h[i] = b0 + i < chunks ? chunk_hist[static_cast<size_t>(b0 + i) * E + e] : 0;
+#pragma unroll
+            for (int i = 0; i < kScanBatch; ++i) {
+                if (b0 + i < chunks) chunk_hist[static_cast<size_t>(b0 + i) * E + e] = base;
+                base += h[i];
+            }
+        }
     }
     if (e == 0) offsets[E] = start[E];
 }
