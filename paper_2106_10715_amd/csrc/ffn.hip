@@ -280,8 +280,17 @@ __device__ inline void static_for(F&& f) {
 // the LDS writes of the whole tile stalls the wave for their full latency.
 // Loads (or LDS writes) done after the units 0..u of a step that spreads n of them evenly over U units:
 constexpr int loads_upto(int u, int n, int U) { return u < 0 ? 0 : ((u + 1) * n + U - 1) / U < n ? ((u + 1) * n + U - 1) / U : n; }
-// The staging writes (one per row block) go into the units before the last one, which holds the barrier.
-constexpr int writes_upto(int u, int n, int U) { return loads_upto(u, n, U - 1); }
+// The staging writes (one per row block) go into the units before the last one, which holds the barrier:
+// spread evenly, except that one or two row blocks are staged as late as that allows.  Their steps are so
+// short (one or two MFMAs per unit) that the step time is the time their activation loads take to arrive,
+// and every unit the write waits is lead for the load.
+constexpr int writes_upto(int u, int n, int U) {
+    if (n <= 2) {
+        const int done = u - (U - 1 - n) + 1;
+        return done < 0 ? 0 : (done > n ? n : done);
+    }
+    return loads_upto(u, n, U - 1);
+}
 constexpr int unit_of_write(int w, int n, int U) {
     int u = 0;
     while (writes_upto(u, n, U) <= w) ++u;
