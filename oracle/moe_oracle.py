@@ -34,6 +34,8 @@ computed values, invariants).
 from __future__ import annotations
 
 import math
+from fractions import Fraction
+from functools import cmp_to_key
 from typing import Callable, NamedTuple, Optional, Tuple
 
 import numpy as np
@@ -98,11 +100,59 @@ def exact_logits_row(xt: np.ndarray, Wg: np.ndarray, bias: Optional[np.ndarray] 
     return out
 
 
+def exact_dot(xt: np.ndarray, col: np.ndarray, bias_e: Optional[float] = None) -> Fraction:
+    """sum_i xt[i] col[i] (+ bias_e) as an exact rational: every float is an integer times a power of two,
+    so the products and their sum are formed in integer arithmetic with no rounding anywhere."""
+    mx, ex = np.frexp(np.asarray(xt, dtype=np.float64))
+    mw, ew = np.frexp(np.asarray(col, dtype=np.float64))
+    ix = np.ldexp(mx, 53).astype(np.int64).tolist()          # 53-bit integer significands, exact
+    iw = np.ldexp(mw, 53).astype(np.int64).tolist()
+    sh = (ex.astype(np.int64) + ew.astype(np.int64)).tolist()
+    low = min(sh) if sh else 0
+    total = 0
+    for a, b, s in zip(ix, iw, sh):
+        if a and b:
+            total += (a * b) << (s - low)
+    out = Fraction(total) * Fraction(2) ** (low - 106)
+    if bias_e is not None:
+        out += Fraction(float(bias_e))
+    return out
+
+
 def _ranked(L: np.ndarray, k: int):
     order = np.argsort(-L, axis=1, kind="stable")   # descending logit, equal logits keep ascending expert index
     top = np.take_along_axis(L, order[:, :min(k + 1, L.shape[1])], axis=1)
     gaps = top[:, :-1] - top[:, 1:] if top.shape[1] > 1 else np.full((L.shape[0], 1), np.inf)
     return order, top, gaps.min(axis=1)
+
+
+def _rank_exactly(Lt: np.ndarray, xt: np.ndarray, W64: np.ndarray, bias: Optional[np.ndarray], k: int):
+    """Gate order of one token whose logits Lt are correctly rounded exact sums.  Rounding is monotone, so
+    different floats are ordered like the exact values; only experts whose floats coincide are compared as
+    exact rationals (they may still differ by less than the rounding), and a tie that survives goes to the
+    lower expert index.  Returns (order, smallest exact gap between consecutive ranks 0..k)."""
+    E = Lt.shape[0]
+    exact = {}
+
+    def value(e):
+        if e not in exact:
+            exact[e] = exact_dot(xt, W64[:, e], None if bias is None else bias[e])
+        return exact[e]
+
+    def before(a, b):
+        if Lt[a] != Lt[b]:
+            return -1 if Lt[a] > Lt[b] else 1
+        va, vb = value(a), value(b)
+        if va != vb:
+            return -1 if va > vb else 1
+        return -1 if a < b else 1
+
+    order = sorted(range(E), key=cmp_to_key(before))
+    gap = math.inf
+    for r in range(min(k + 1, E) - 1):
+        a, b = order[r], order[r + 1]
+        gap = min(gap, float(value(a) - value(b)) if Lt[a] == Lt[b] else float(Lt[a] - Lt[b]))
+    return order, gap
 
 
 def route(x: np.ndarray, Wg: np.ndarray, k: int = 1, bias: Optional[np.ndarray] = None,
@@ -111,7 +161,8 @@ def route(x: np.ndarray, Wg: np.ndarray, k: int = 1, bias: Optional[np.ndarray] 
 
     The ranking is the one exact arithmetic gives.  The matrix product is a library matmul whose
     rounding error is at most about d * 2^-53 * |x_t| * |W_g column|; any token whose k+1 best
-    logits are not separated by more than that bound is re-evaluated with exact_logits_row.
+    logits are not separated by more than that bound gets its logits as correctly rounded exact sums
+    (exact_logits_row) and is ranked by _rank_exactly.
     """
     x64 = np.asarray(x, dtype=np.float64)
     W64 = np.asarray(Wg, dtype=np.float64)
@@ -123,11 +174,14 @@ def route(x: np.ndarray, Wg: np.ndarray, k: int = 1, bias: Optional[np.ndarray] 
     d = x64.shape[1]
     col = np.sqrt((W64 * W64).sum(axis=0)).max() if E else 0.0
     bound = (d + 4) * 2.0 ** -53 * (np.sqrt((x64 * x64).sum(axis=1)) * col + np.abs(top).max(axis=1))
-    for t in np.nonzero(margin <= 4.0 * bound)[0]:
+    close = np.nonzero(margin <= 4.0 * bound)[0]
+    for t in close:
         L[t] = exact_logits_row(x64[t], W64, bias)
     order, top, margin = _ranked(L, k)
+    for t in close:
+        order[t], margin[t] = _rank_exactly(L[t], x64[t], W64, bias, k)
     idx = order[:, :k].astype(np.int32)
-    sel = top[:, :k]
+    sel = np.take_along_axis(L, order[:, :k], axis=1)
     if renorm:
         ex = np.exp(sel - sel[:, :1])
         w = ex / ex.sum(axis=1, keepdims=True)
