@@ -58,6 +58,10 @@ typedef struct moe_cfg {
                         MOE_GATE_HASH: the gate of Section 2.3 read literally as a locality sensitive hash:
                         W_g is [d, log2 E], bit j of the expert id is set when x.W_g[:, j] > 0 (an exactly
                         zero projection gives 0), weight 1; needs E a power of two >= 2, k = 1, no bias */
+    int32_t gate_packed; /* 0: W_g arguments are the matrix itself, [d, E] (hashing gate: [d, log2 E]), row-major;
+                            every call that routes re-packs it into the workspace first.
+                            1: W_g arguments point at the block moe_pack_gate wrote (the gate is frozen, Section 2.3,
+                            so it is packed once, like the experts) */
 } moe_cfg;
 
 typedef struct moe_stream_ctx moe_stream_ctx;   /* opaque: state of the host-streamed expert mode */
@@ -88,11 +92,25 @@ int moe_pack_weights(const moe_cfg* cfg, const void* W_in_e, const void* W_gate_
                      void* packed_e, void* stream);
 
 /*
+ * The gate in the form the gate kernel reads (Section 2.3: the gate is a random projection that is not
+ * trained any further, so this is done once per model, not once per call).
+ *   W_g: device, dtype, [d, E] row-major (hashing gate: [d, log2 E]), 16-byte aligned.
+ *   gate_packed: device, moe_gate_bytes() bytes, 256-byte aligned, must not overlap W_g; written on `stream`.
+ * bf16: the matrix in 1 KiB fragments in the operand order of the 32x32x16 bf16 matrix instruction, columns
+ * padded with zeros to a multiple of 32, followed by the sum of squares of every 64-row group of every column
+ * (fp32; the gate kernel bounds its rounding error with them).  fp32: the matrix unchanged.
+ * cfg->gate_packed is ignored here; set it to 1 in the cfg of the calls that are given the block as W_g.
+ */
+int moe_gate_bytes(const moe_cfg* cfg, size_t* bytes);
+int moe_pack_gate(const moe_cfg* cfg, const void* W_g, void* gate_packed, void* stream);
+
+/*
  * Gate (Sections 2.1, 2.3): logits L = x W_g (+ gate_bias); per token the k largest logits, slot j
  * ordered by descending logit, every tie resolved to the lower expert index; combine weights per
  * cfg->renorm.  The selection equals the one exact arithmetic on the stored inputs would make: tokens
  * whose fp32 logits are closer than the fp32 error bound are re-evaluated in fp64 inside the kernel.
- *   x [T, d], W_g [d, E]: device, dtype.   gate_bias [E]: device fp32, or NULL.
+ *   x [T, d]: device, dtype.  W_g: device, the matrix [d, E] in dtype or, with cfg->gate_packed, the block
+ *   written by moe_pack_gate.   gate_bias [E]: device fp32, or NULL.
  *   idx [T, k] int32, w [T, k] fp32: device, written.
  */
 int moe_route(const moe_cfg* cfg, const void* x, const void* W_g, const float* gate_bias,
@@ -122,8 +140,10 @@ int moe_expert_ffn(const moe_cfg* cfg, const void* Xp, const int32_t* offsets, c
                    void* Yp, void* ws, void* stream);
 
 /*
- * Weighted un-permute: y[t, :] = sum_{j<k} w[t, j] * Yp[inv[t*k + j], :], summed in slot order in
- * fp32, rounded once to dtype.   Yp [T*k, d], inv [T*k], w [T, k]: device;  y [T, d]: device, written.
+ * Weighted un-permute (Section 2.1: the output of the selected expert takes the place of the feed-forward
+ * output of the token; with k experts per token, their weighted sum): y[t, :] = sum_{j<k} w[t, j] *
+ * Yp[inv[t*k + j], :], summed in slot order in fp32, rounded once to dtype.
+ *   Yp [T*k, d], inv [T*k], w [T, k]: device;  y [T, d]: device, written.
  */
 int moe_combine(const moe_cfg* cfg, const void* Yp, const int32_t* inv, const float* w, void* y, void* stream);
 
@@ -137,11 +157,15 @@ int moe_combine(const moe_cfg* cfg, const void* Yp, const int32_t* inv, const fl
  *   on the host.
  *   Streamed mode (sctx != NULL, W_packed ignored): the experts live in pinned host memory (Section 6).
  *   After route + permute the call copies counts[E] to the host and waits for it (the host must know
- *   which experts have tokens; Section 6.2 sizes an expert's compute by its token count), then for each
- *   non-empty expert, in ascending id, copies its packed block into one of the K device slots on the
- *   context's copy stream while earlier experts compute on `stream`; events order copy-before-compute
- *   and compute-before-slot-reuse.  Experts without tokens are not loaded.  Every call reloads every
- *   non-empty expert.  The call returns with the remaining work enqueued on `stream`.
+ *   which experts have tokens; Section 6.2 sizes an expert's compute by its token count), then runs the
+ *   non-empty experts in the order of the context (ascending id unless moe_stream_ctx_set_order chose the
+ *   greedy order of Section 6.2): each expert's packed block is copied into one of the K device slots on the
+ *   context's copy stream while earlier experts compute on `stream`; events order copy-before-compute and
+ *   compute-before-slot-reuse.  Experts without tokens are not loaded.  Every call loads every non-empty
+ *   expert, unless moe_stream_ctx_keep_experts lets the slots keep theirs between calls (then only experts
+ *   no slot holds are loaded).  The call returns with the remaining work enqueued on `stream`.  If the
+ *   call fails half-way, the context forgets what its slots hold (nothing is taken for resident that may
+ *   not have been copied).
  *   Results are bitwise identical in both modes.
  *   Resident calls consist of kernel launches only and can be recorded into a HIP graph; with more than 32
  *   experts, run one call outside the capture first (the gate kernel raises its LDS limit once per device).
@@ -161,7 +185,7 @@ int moe_stream_ctx_create(const moe_cfg* cfg, const void* host_experts, size_t e
 int moe_stream_ctx_destroy(moe_stream_ctx* sctx);
 
 /*
- * Execution order of offloaded experts (Section 6.2, "Scheduling Strategy for Offloading").
+ * Execution order of offloaded experts (Section 6.2, the part on scheduling offloaded experts).
  *
  * With alpha_i the computation time of expert i (proportional to its token count), beta the loading
  * time of one expert (the same for all) and K the number of experts loads may run ahead, the paper
@@ -199,8 +223,8 @@ int moe_stream_ctx_set_order(moe_stream_ctx* sctx, int32_t policy, double tokens
 int moe_stream_ctx_last_order(const moe_stream_ctx* sctx, int32_t* order, int32_t* n_order, int32_t* satisfiable);
 
 /*
- * Experts that stay resident (Section 6.2: K experts can reside in GPU memory; K "configured or
- * automatically inferred").
+ * Experts that stay resident (Section 6.2: the device holds K experts at a time, K set by the caller or
+ * derived from the memory there is).
  *
  * moe_stream_slots_that_fit: the K a context can be given on the current device: how many packed experts
  * of this cfg fit into the free device memory minus reserve_bytes, at most 64 and at most E.
@@ -218,8 +242,9 @@ int moe_stream_ctx_last_order(const moe_stream_ctx* sctx, int32_t* order, int32_
  *
  * moe_stream_ctx_prefetch(sctx, e): start loading expert e into a slot now, on the copy stream, unless a
  * slot holds it (needs keeping switched on).  Meant for a stack of layers: while layer l computes, the
- * caller prefetches the expert it expects layer l+1 to run first, so that "no expert waits for its
- * parameters except the first" holds once per model rather than once per layer.  Returns at once.
+ * caller prefetches the expert it expects layer l+1 to run first, so that the one load nothing hides
+ * (Section 6.2: only the first expert waits for its parameters) is paid once per model rather than once
+ * per layer.  Returns at once.
  *
  * moe_plan_slots is the replacement rule itself as a pure host function (all arrays host memory):
  *   order [n] experts in execution order;  slot_expert [K] in/out, -1 = empty;  slot_tick [K] in/out, when
@@ -239,30 +264,30 @@ int moe_plan_slots(const int32_t* order, int32_t n, int32_t K, int32_t* slot_exp
 int moe_stream_ctx_stats(moe_stream_ctx* sctx, int32_t* n_loaded, size_t* bytes, float* copy_ms);
 
 /*
- * Measurement aid: per-stage timing of resident moe_layer_forward calls.  After
- * moe_stage_timing_enable(max_calls) each of the next max_calls resident calls records hipEvents on
- * its stream around its five stages (route, permute, expert up-projection kernel, expert
- * down-projection kernel, combine; Sections 2.1 and 6.2 name the stages).  moe_stage_timing_read waits
- * for the recorded calls and writes ms[call][5] (host, row-major, at most capacity_calls rows);
- * n_calls receives the number of calls recorded.  Process-wide state, not thread-safe; events are the
- * only resources held and moe_stage_timing_disable releases them.
+ * Measurement aid: a resident moe_layer_forward that also records HIP events on `stream` around its stages
+ * (Sections 2.1 and 6.2 name them: route, batch by expert, expert FFNs, combine) into a timer object the
+ * caller owns.  The hot entry point itself keeps no timing state.
+ *
+ * moe_timer_create(max_calls, mode): room for max_calls (1..4096) timed calls.
+ *   MOE_TIME_STAGES     events around all five stages (route, permute, expert up-projection kernel, expert
+ *                       down-projection kernel, combine); each event between two kernels costs the call a
+ *                       few microseconds of idle time
+ *   MOE_TIME_UP_KERNEL  two events only, right before and right after the expert up-projection kernel
+ * moe_layer_forward_timed: the same work, on the same kernels, as resident moe_layer_forward(cfg, ..., NULL, y, ws,
+ *   stream), plus the events; once the timer is full it records nothing more.  A timer must not be used from two
+ *   threads at once.
+ * moe_timer_read waits for the recorded calls; ms is host memory, row-major [call][5] (MOE_TIME_STAGES) or
+ *   [call] (MOE_TIME_UP_KERNEL), at most capacity_calls rows are written; *n_calls = calls recorded.
+ * moe_timer_reset forgets the recorded calls (the events are kept); moe_timer_destroy releases everything.
  */
-int moe_stage_timing_enable(int32_t max_calls);
-int moe_stage_timing_read(float* ms, int32_t capacity_calls, int32_t* n_calls);
-int moe_stage_timing_disable(void);
-
-/*
- * The same for the dominant kernel alone: only two events per call, right before and right after the
- * expert up-projection kernel of resident bf16 calls (an event between two kernels costs a few
- * microseconds of idle time, so timing every stage slows the call it measures).
- * moe_up_kernel_timing_read writes ms[call] (host, at most capacity_calls values).  Shares its state
- * with the per-stage timing: enabling one replaces the other, moe_stage_timing_disable ends both.
- */
-int moe_up_kernel_timing_enable(int32_t max_calls);
-/* After enabling: time only the resident calls number 0, every, 2 every, ... from now on (up to max_calls of
- * them), so that a long timed run pays the idle time of the two events in a fraction of its calls. */
-int moe_up_kernel_timing_every(int32_t every);
-int moe_up_kernel_timing_read(float* ms, int32_t capacity_calls, int32_t* n_calls);
+typedef struct moe_timer moe_timer;
+enum { MOE_TIME_STAGES = 0, MOE_TIME_UP_KERNEL = 1 };
+int moe_timer_create(int32_t max_calls, int32_t mode, moe_timer** out);
+int moe_timer_destroy(moe_timer* timer);
+int moe_timer_reset(moe_timer* timer);
+int moe_timer_read(moe_timer* timer, float* ms, int32_t capacity_calls, int32_t* n_calls);
+int moe_layer_forward_timed(const moe_cfg* cfg, const void* x, const void* W_g, const float* gate_bias,
+                            const void* W_packed, void* y, void* ws, void* stream, moe_timer* timer);
 
 #ifdef __cplusplus
 }

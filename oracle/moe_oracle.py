@@ -193,8 +193,8 @@ def route(x: np.ndarray, Wg: np.ndarray, k: int = 1, bias: Optional[np.ndarray] 
 
 
 def route_hash(x: np.ndarray, Wh: np.ndarray) -> Routing:
-    """Sign-bit reading of Section 2.3's gate ("a random projection as a locality sensitive hashing
-    function"): the hidden state is projected on b random directions W_h[d, b] and the signs of the b
+    """Sign-bit reading of Section 2.3's gate (which the paper describes as a random projection that serves
+    as a hashing function of the locality sensitive kind): the hidden state is projected on b random directions W_h[d, b] and the signs of the b
     projections, read as a binary number, name one of E = 2^b experts:
         idx[t] = sum_j [ x_t . W_h[:, j] > 0 ] * 2^j,        weight 1.
     A projection that is exactly zero gives bit 0.  As in route(), the decision is the one exact

@@ -3,7 +3,7 @@
 TEST INFRASTRUCTURE ONLY.  Nothing on the product path may import this module; it shares no code
 with the library's host scheduler.
 
-What it states (CPM-2 paper, arxiv 2106.10715, Section 6.2, "Scheduling Strategy for Offloading"):
+What it states (CPM-2 paper, arxiv 2106.10715, Section 6.2, the part on scheduling offloaded experts):
 
 * expert i needs alpha_i seconds of computation (its floating-point operations over the peak rate,
   proportional to its token count) and every expert needs the same beta seconds of parameter

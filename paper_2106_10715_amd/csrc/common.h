@@ -29,6 +29,13 @@ void clear_error();
 
 int check_cfg(const moe_cfg* cfg);
 
+// What the launchers need to know about a device, looked up once per device (under a lock) and kept.
+struct DeviceInfo {
+    int compute_units = 256;
+};
+// The current device and its entry; MOE_ERR_HIP (message recorded) if the device cannot be queried.
+int device_info(int* device, const DeviceInfo** info);
+
 inline size_t elem_size(const moe_cfg& c) { return c.dtype == MOE_BF16 ? 2 : 4; }
 inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }

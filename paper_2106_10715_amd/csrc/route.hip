@@ -8,6 +8,8 @@
 // too close to call (products of two bf16 or two fp32 values are exact in fp64).
 #include "common.h"
 
+#include <atomic>
+
 namespace moe {
 namespace {
 
@@ -384,7 +386,7 @@ constexpr size_t gate_tile_bytes() { return static_cast<size_t>(gate_parts<NB>()
 // A short batch gets more, smaller blocks this way: a block's time is mostly its own loads through one
 // compute unit plus a selection that is a latency chain per token, and 128 blocks leave half the chip idle.
 template <int NB, int TOK>
-__global__ __launch_bounds__(kGateWaves * 64, (TOK == 32 && NB == 1) ? 4 : 2) void route_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ Wg,
+__global__ __launch_bounds__(kGateWaves * 64, (TOK == 32 && NB == 1) ? 4 : 2) void route_mfma_kernel(const uint16_t* __restrict__ x,
                                                          const uint4* __restrict__ pack, const float* __restrict__ part,
                                                          const float* __restrict__ bias, int32_t* __restrict__ idx,
                                                          float* __restrict__ w, int T, int d, int E, int k, int renorm,
@@ -734,8 +736,30 @@ int gate_columns(const moe_cfg& c) {
 
 size_t route_scratch_bytes(const moe_cfg& c) {
     if (c.dtype != MOE_BF16) return 0;
-    const size_t EP = static_cast<size_t>((c.E + 31) / 32) * 32;
+    const size_t EP = static_cast<size_t>((gate_columns(c) + 31) / 32) * 32;
     return align256(EP * c.d * 2) + align256(static_cast<size_t>(c.d / 64) * EP * 4);
+}
+
+size_t gate_packed_bytes(const moe_cfg& c) {
+    if (c.dtype == MOE_BF16) return route_scratch_bytes(c);
+    return align256(static_cast<size_t>(c.d) * gate_columns(c) * 4);
+}
+
+// The gate in the form the gate kernel reads: bf16, fragments in MFMA operand order followed by the sums of
+// squares of every 64-row group of every column; fp32, the matrix itself.
+int launch_pack_gate(const moe_cfg& c, const void* Wg, void* packed, hipStream_t s) {
+    const int cols = gate_columns(c);
+    if (c.dtype == MOE_BF16) {
+        const int NB = (cols + 31) / 32;
+        const size_t EP = static_cast<size_t>(NB) * 32;
+        float* part = reinterpret_cast<float*>(static_cast<char*>(packed) + align256(EP * c.d * 2));
+        hipLaunchKernelGGL(gate_prep_kernel, dim3(c.d / 64), dim3(256), 0, s, static_cast<const uint16_t*>(Wg), c.d, cols, NB,
+                           static_cast<uint4*>(packed), part);
+        MOE_LAUNCH_CHECK("gate_prep_kernel");
+        return MOE_OK;
+    }
+    MOE_HIP_CHECK(hipMemcpyAsync(packed, Wg, static_cast<size_t>(c.d) * cols * 4, hipMemcpyDeviceToDevice, s));
+    return MOE_OK;
 }
 
 int launch_route(const moe_cfg& c, const void* x, const void* Wg, const float* bias, int32_t* idx, float* w,
@@ -746,29 +770,35 @@ int launch_route(const moe_cfg& c, const void* x, const void* Wg, const float* b
     if (c.dtype == MOE_BF16) {
         const int NB = (cols + 31) / 32;
         const size_t EP = static_cast<size_t>(NB) * 32;
-        uint4* pack = static_cast<uint4*>(scratch);
-        float* part = reinterpret_cast<float*>(static_cast<char*>(scratch) + align256(EP * c.d * 2));
-        hipLaunchKernelGGL(gate_prep_kernel, dim3(c.d / 64), dim3(256), 0, s, static_cast<const uint16_t*>(Wg), c.d, cols, NB,
-                           pack, part);
-        MOE_LAUNCH_CHECK("gate_prep_kernel");
-        int dev = 0, n_cu = 0;
-        MOE_HIP_CHECK(hipGetDevice(&dev));
-        if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0) n_cu = 256;
+        // a gate packed once by the caller (it is frozen: Section 2.3) is read where it lies; else it is packed
+        // into the workspace first, by every call
+        if (!c.gate_packed)
+            if (int rc = launch_pack_gate(c, Wg, scratch, s)) return rc;
+        const char* gate = static_cast<const char*>(c.gate_packed ? Wg : scratch);
+        const uint4* pack = reinterpret_cast<const uint4*>(gate);
+        const float* part = reinterpret_cast<const float*>(gate + align256(EP * c.d * 2));
+        int dev = 0;
+        const DeviceInfo* info = nullptr;
+        if (int rc = device_info(&dev, &info)) return rc;
+        const int n_cu = info->compute_units;
         // as many tokens per block as still give every compute unit a block
         const int tok = (c.T + 31) / 32 >= n_cu ? 32 : (c.T + 15) / 16 >= n_cu ? 16 : 8;
         dim3 grid((c.T + tok - 1) / tok), block(kGateWaves * 64);
 #define MOE_ROUTE_LAUNCH(N, TK)                                                                                       \
     {                                                                                                                 \
-        /* the tiles of more than 32 experts exceed the default LDS limit of a launch: raised once per device */    \
-        if (static int raised_on = -1; gate_tile_bytes<N>() > 48 * 1024 && raised_on != dev) {                        \
+        /* the tiles of more than 32 experts exceed the default LDS limit of a launch: raised once per device and   \
+           kernel (a bit per device; two threads that both find it clear both raise it, which is harmless) */       \
+        static std::atomic<uint64_t> raised{0};                                                                       \
+        const uint64_t bit = uint64_t(1) << (dev & 63);                                                               \
+        if (gate_tile_bytes<N>() > 48 * 1024 && (dev >= 64 || !(raised.load(std::memory_order_acquire) & bit))) {     \
             MOE_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&route_mfma_kernel<N, TK>),               \
                                               hipFuncAttributeMaxDynamicSharedMemorySize,                             \
                                               static_cast<int>(gate_tile_bytes<N>())));                               \
-            raised_on = dev;                                                                                          \
+            if (dev < 64) raised.fetch_or(bit, std::memory_order_release);                                            \
         }                                                                                                             \
         hipLaunchKernelGGL((route_mfma_kernel<N, TK>), grid, block, gate_tile_bytes<N>(), s,                          \
-                           static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(Wg), pack, part, bias, idx,  \
-                           w, c.T, c.d, cols, c.k, c.renorm, hash);                                                   \
+                           static_cast<const uint16_t*>(x), pack, part, bias, idx, w, c.T, c.d, cols, c.k, c.renorm,  \
+                           hash);                                                                                     \
     }
 #define MOE_ROUTE_CASE(N)                                                                                             \
     case N:                                                                                                           \

@@ -1,4 +1,4 @@
-// Execution order of offloaded experts (CPM-2 Section 6.2, "Scheduling Strategy for Offloading").
+// Execution order of offloaded experts (CPM-2 Section 6.2, the part on scheduling offloaded experts).
 //
 // Expert i needs alpha_i of computation, proportional to its token count n_i, and every expert the same
 // beta of parameter loading; the order o_1..o_T should satisfy for every position t

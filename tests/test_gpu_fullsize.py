@@ -1,11 +1,17 @@
 """Parity at the full sizes of the measured configurations, in the launch configuration the bench
 times (resident moe_layer_forward; host-streamed for the offload case).
 
-Routing, counts, offsets and the permutation are compared with the oracle in full (they are cheap on
-the CPU).  The expert FFN output is compared on sampled rows the oracle evaluates one by one (first,
-last and random rows of the heaviest, the lightest and a few random non-empty experts); the combine is
-checked on sampled tokens from the GPU's own Yp; and the fused entry point must reproduce the staged
-calls bit for bit."""
+What the layer computes is fixed by Section 2.1 (every token goes to the expert its gate picks, whose
+output stands in for the FFN output), Section 6.2 (tokens batched by expert) and Table 1 (d_model 4096,
+d_ff 10240, three matrices per expert).  Routing, counts, offsets and the permutation are compared with
+the oracle in full and bit for bit.  At T 2048 / 8 experts and T 4096 / 32 experts (and the streamed
+T 512 / T 8192 runs of the same layer) the WHOLE of Yp and y is compared with the fp64 oracle, expert by
+expert: normalised L2 per expert segment, per row (worst row printed) and over the whole tensor.  At the
+two large workloads the oracle evaluates the rows at every tile seam of a few experts (first and last
+row of each row tile the kernel cuts the segment into, the start of the last 32-row block, random rows)
+and whole tokens whose experts are among them; y is always checked against what the oracle makes of its
+own Yp, weights and inverse permutation.  The fused entry point must reproduce the staged calls bit
+for bit."""
 import numpy as np
 import pytest
 import torch
@@ -17,10 +23,18 @@ from paper_2106_10715_amd import harness as H
 
 pytestmark = pytest.mark.gpu
 
+TOL = 1e-2          # normalised L2 of bf16 outputs against the fp64 oracle on the same stored inputs
+
 
 def rel_l2(got, ref):
     den = np.linalg.norm(ref)
     return float(np.linalg.norm(np.asarray(got, np.float64) - ref) / (den if den > 0 else 1.0))
+
+
+def row_l2(got, ref):
+    """Normalised L2 of every row."""
+    den = np.linalg.norm(ref, axis=1)
+    return np.linalg.norm(np.asarray(got, np.float64) - ref, axis=1) / np.where(den > 0, den, 1.0)
 
 
 def staged(L):
@@ -37,15 +51,8 @@ def staged(L):
     return s
 
 
-def check_full_size(wl, L, n_experts=5, rows_per_expert=6):
-    rng = np.random.default_rng(wl.seed)
-    x = W.gen_x(wl)
-    Wg, bias = W.gen_gate(wl)
-    s = staged(L)
-    M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)
-    torch.cuda.synchronize()
-    assert torch.equal(L.y, s["y"]), "fused entry point differs from the staged calls"
-
+def check_integers(wl, s, x, Wg, bias):
+    """Gate and batching against the oracle, everything, bit for bit (weights to fp32 accuracy)."""
     r = O.route(x, Wg, wl.k, bias, wl.renorm)
     p = O.permute(x, r.idx, wl.E)
     print(f"\n[{wl.name}] min routing margin {r.margin.min():.3e}; counts max {p.counts.max()} min {p.counts.min()} "
@@ -56,35 +63,120 @@ def check_full_size(wl, L, n_experts=5, rows_per_expert=6):
     assert np.array_equal(s["offsets"].cpu().numpy(), p.offsets)
     assert np.array_equal(s["perm"].cpu().numpy(), p.perm)
     assert np.array_equal(s["inv"].cpu().numpy(), p.inv)
+    rng = np.random.default_rng(wl.seed)
     rows = rng.choice(wl.A, size=min(wl.A, 1500), replace=False)
     assert np.array_equal(H.to_f64(s["Xp"][torch.from_numpy(rows).cuda()]), p.Xp[rows])
     if wl.n_dead:
         assert (p.counts == 0).sum() >= wl.n_dead
-    assert bool(torch.isfinite(s["y"].float()).all())
+    return r, p
 
-    live = np.nonzero(p.counts > 0)[0]
-    pick = {int(live[np.argmax(p.counts[live])]), int(live[np.argmin(p.counts[live])])}
-    pick |= set(int(e) for e in rng.choice(live, size=min(len(live), n_experts), replace=False))
+
+def oracle_whole_layer(wl, x, r, p):
+    """Yp and y of the whole batch by the oracle, one expert's weights in memory at a time."""
     pool = W.make_pool()
-    worst = 0.0
     try:
-        for e in sorted(pick)[:n_experts + 2]:
-            lo, hi = int(p.offsets[e]), int(p.offsets[e + 1])
-            rr = {lo, hi - 1} | set(int(v) for v in rng.integers(lo, hi, size=rows_per_expert))
-            rr = np.array(sorted(rr))
-            ref = O.expert_ffn_rows(p.Xp[rr], *W.gen_expert(wl, e, pool))
-            got = H.to_f64(s["Yp"][torch.from_numpy(rr).cuda()])
-            err = rel_l2(got, ref)
-            worst = max(worst, err)
-            assert err <= 1e-2, f"expert {e} ({hi - lo} rows): normalised L2 {err:.3e}"
+        Yp = O.expert_ffn(p.Xp, p.offsets, lambda e: W.gen_expert(wl, e, pool))
     finally:
         pool.shutdown()
-    toks = rng.choice(wl.T, size=min(wl.T, 1024), replace=False)
-    Yp64 = lambda rws: H.to_f64(s["Yp"][torch.from_numpy(rws).cuda()])
+    return Yp, O.combine(Yp, p.inv, r.w)
+
+
+def compare_whole(name, what, got, ref, offsets=None):
+    """Whole tensor, every expert segment (if offsets are given) and every row within TOL; prints the worst."""
+    total = rel_l2(got, ref)
+    rows = row_l2(got, ref)
+    worst = int(rows.argmax())
+    msg = f"[{name}] {what}: whole tensor {total:.3e}, worst row {worst} {rows[worst]:.3e}"
+    if offsets is not None:
+        seg = [(rel_l2(got[lo:hi], ref[lo:hi]), e) for e, (lo, hi) in enumerate(zip(offsets[:-1], offsets[1:])) if hi > lo]
+        msg += f", worst expert segment {max(seg)[1]} {max(seg)[0]:.3e}"
+        assert max(seg)[0] <= TOL, msg
+    print(msg)
+    assert total <= TOL and rows[worst] <= TOL, msg
+
+
+def check_whole(wl, L):
+    """Every element of Yp and y against the oracle (the workloads the oracle finishes in seconds)."""
+    x = W.gen_x(wl)
+    Wg, bias = W.gen_gate(wl)
+    s = staged(L)
+    M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(L.y, s["y"]), "fused entry point differs from the staged calls"
+    r, p = check_integers(wl, s, x, Wg, bias)
+    Yp_ref, y_ref = oracle_whole_layer(wl, x, r, p)
+    compare_whole(wl.name, "Yp", H.to_f64(s["Yp"]), Yp_ref, p.offsets)
+    compare_whole(wl.name, "y", H.to_f64(L.y), y_ref)
+    return s
+
+
+def seam_rows(n):
+    """Rows of an n-row expert segment at the seams of the kernel's tiling: the segment is cut into
+    ceil(n / 256) tiles of equal height (a multiple of 32); first and last row of every tile, and the start
+    of the last 32-row block."""
+    tiles = (n + 255) // 256
+    per = min(256, ((n + tiles - 1) // tiles + 31) // 32 * 32)
+    out = {0, n - 1, (n - 1) // 32 * 32}
+    for t in range(tiles):
+        out |= {min(t * per, n - 1), min((t + 1) * per, n) - 1}
+    return out
+
+
+def check_sampled(wl, L, n_experts=4, random_rows=6, n_tokens=48):
+    """The large workloads: integers in full; Yp on the seam rows and random rows of a few experts (the two
+    heaviest, the lightest, random ones); y on whole tokens all of whose experts are among those, built from
+    the oracle's own Yp rows, weights and inverse permutation."""
+    rng = np.random.default_rng(wl.seed)
+    x = W.gen_x(wl)
+    Wg, bias = W.gen_gate(wl)
+    s = staged(L)
+    M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(L.y, s["y"]), "fused entry point differs from the staged calls"
+    assert bool(torch.isfinite(s["y"].float()).all())
+    r, p = check_integers(wl, s, x, Wg, bias)
+
+    live = np.nonzero(p.counts > 0)[0]
+    by_load = live[np.argsort(-p.counts[live], kind="stable")]
+    pick = [int(by_load[0]), int(by_load[1]), int(by_load[-1])]
+    pick += [int(e) for e in rng.choice(live, size=min(len(live), n_experts), replace=False)]
+    pick = sorted(set(pick))
     inv2 = p.inv.reshape(wl.T, wl.k)
-    y_ref = sum(r.w[toks, j:j + 1].astype(np.float64) * Yp64(inv2[toks, j]) for j in range(wl.k))
-    assert rel_l2(H.to_f64(s["y"][torch.from_numpy(toks).cuda()]), y_ref) <= 4e-3     # one bf16 rounding
-    print(f"[{wl.name}] worst sampled expert-FFN normalised L2 {worst:.3e}")
+    in_pick = np.isin(r.idx, pick).all(axis=1)
+    toks = np.nonzero(in_pick)[0]
+    toks = np.sort(rng.choice(toks, size=min(len(toks), n_tokens), replace=False))
+    assert len(toks) > 0
+    need = {e: set() for e in pick}
+    for t in toks:
+        for j in range(wl.k):
+            need[int(r.idx[t, j])].add(int(inv2[t, j]))
+    pool = W.make_pool()
+    Yp_ref = {}                                   # batched row -> oracle output row
+    worst_row, n_rows = 0.0, 0
+    try:
+        for e in pick:
+            lo, hi = int(p.offsets[e]), int(p.offsets[e + 1])
+            rows = {lo + v for v in seam_rows(hi - lo)} | {int(v) for v in rng.integers(lo, hi, size=random_rows)} | need[e]
+            rows = np.array(sorted(rows))
+            ref = O.expert_ffn_rows(p.Xp[rows], *W.gen_expert(wl, e, pool))
+            got = H.to_f64(s["Yp"][torch.from_numpy(rows).cuda()])
+            err = row_l2(got, ref)
+            assert err.max() <= TOL, f"expert {e} ({hi - lo} rows): row {rows[err.argmax()] - lo} normalised L2 {err.max():.3e}"
+            assert rel_l2(got, ref) <= TOL
+            worst_row = max(worst_row, float(err.max()))
+            n_rows += len(rows)
+            Yp_ref.update({int(rw): ref[i] for i, rw in enumerate(rows)})
+    finally:
+        pool.shutdown()
+    y_ref = np.zeros((len(toks), wl.d))
+    for i, t in enumerate(toks):
+        for j in range(wl.k):
+            y_ref[i] += np.float64(r.w[t, j]) * Yp_ref[int(inv2[t, j])]
+    y_got = H.to_f64(L.y[torch.from_numpy(toks).cuda()])
+    y_err = row_l2(y_got, y_ref)
+    assert y_err.max() <= TOL and rel_l2(y_got, y_ref) <= TOL
+    print(f"[{wl.name}] {n_rows} Yp rows of experts {pick} (all tile seams): worst row {worst_row:.3e}; "
+          f"{len(toks)} whole tokens of y against the oracle's own Yp: worst {y_err.max():.3e}")
     return s
 
 
@@ -99,13 +191,13 @@ def c3_layer():
 def test_c2_resident_full_size():
     wl = W.CONFIGS["c2"]
     L = H.build_layer(wl)
-    check_full_size(wl, L)
+    check_whole(wl, L)
     del L
     torch.cuda.empty_cache()
 
 
 def test_c3_resident_full_size(c3_layer):
-    check_full_size(W.CONFIGS["c3"], c3_layer)
+    check_whole(W.CONFIGS["c3"], c3_layer)
 
 
 @pytest.mark.parametrize("name", ["c4a", "c4b"])
@@ -113,7 +205,8 @@ def test_c4_streamed_equals_resident_full_size(c3_layer, name):
     wl = W.CONFIGS[name]                        # same weights as c3 (same seed), other token counts
     base = c3_layer
     cfg = H.cfg_of(wl)
-    x = H.to_device(W.gen_x(wl), wl.dtype)
+    xs = W.gen_x(wl)
+    x = H.to_device(xs, wl.dtype)
     ws = torch.empty(M.moe_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
     y_res = torch.empty((wl.T, wl.d), dtype=torch.bfloat16, device="cuda")
     y_str = torch.full((wl.T, wl.d), float("nan"), dtype=torch.bfloat16, device="cuda")
@@ -127,21 +220,18 @@ def test_c4_streamed_equals_resident_full_size(c3_layer, name):
     st = ctx.stats()
     print(f"\n[{wl.name}] streamed: {st['n_loaded']} experts, {st['bytes'] / st['copy_ms'] / 1e6:.1f} GB/s over the copy window")
     ctx.close()
-    # and the resident result itself is right: sampled tokens against the oracle (top-1: y = FFN_e(x))
+    # and the streamed result is the layer's: every element of y against the oracle
     Wg, _ = W.gen_gate(wl)
-    xs = W.gen_x(wl)
     r = O.route(xs, Wg, 1)
-    rng = np.random.default_rng(0)
-    e = int(r.idx[0, 0])
-    toks = np.nonzero(r.idx[:, 0] == e)[0][:6]
-    ref = O.expert_ffn_rows(xs[toks], *W.gen_expert(wl, e))
-    assert rel_l2(H.to_f64(y_res[torch.from_numpy(toks).cuda()]), ref) <= 1e-2
+    p = O.permute(xs, r.idx, wl.E)
+    _, y_ref = oracle_whole_layer(wl, xs, r, p)
+    compare_whole(wl.name, "y (streamed)", H.to_f64(y_str), y_ref)
 
 
 def test_c5_zipf_top2_full_size():
     wl = W.CONFIGS["c5"]
     L = H.build_layer(wl)
-    s = check_full_size(wl, L, n_experts=4)
+    s = check_sampled(wl, L, n_experts=3)
     counts = s["counts"].cpu().numpy()
     assert counts.max() > 20 * max(1, counts[counts > 0].min())      # the load really is skewed
     del L
@@ -151,7 +241,7 @@ def test_c5_zipf_top2_full_size():
 def test_c6_token_throughput_regime_full_size():
     wl = W.CONFIGS["c6"]
     L = H.build_layer(wl)
-    s = check_full_size(wl, L, n_experts=3)
+    s = check_sampled(wl, L, n_experts=2)
     counts = s["counts"].cpu().numpy()
     assert counts.min() > 1500                                       # every expert is in the compute-bound regime
     del L
