@@ -7,7 +7,9 @@ A step is one moe_layer_forward (route -> permute -> expert FFNs -> combine) ove
 seeded synthetic tokens that is already resident in HBM.  Prints ONE JSON line: whole-layer
 tokens/s, the roofline figure of the dominant kernel (the fused gate/in up-projection of the expert
 FFNs; duration measured with HIP events on the launch stream inside every tenth timed step), per-stage
-times, and the CPU oracle timed on the host cores on a bounded sample of the same workload.
+times, the same step replayed from a captured HIP graph, a short host-streamed leg on the same weights
+(host-to-device rate and load/compute overlap: the other half of the metric), and the CPU oracle timed on
+the host cores on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -35,6 +37,10 @@ def parse():
                          "GPU run 2-3 %% slower than the steady state; 5 streamed)")
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4a", "c4b", "c5", "c6"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-streaming-leg", action="store_true",
+                    help="resident c3 run: leave out the short host-streamed leg (T 512, the same weights) that fills the "
+                         "'streaming' record")
+    ap.add_argument("--no-graph", action="store_true", help="resident run: leave out the captured-graph replay")
     ap.add_argument("--tokens", type=int, default=None,
                     help="run the workload's layer on this many tokens instead of its own count (a sweep over batch sizes; "
                          "the figure the workload is quoted on is the one without this option)")
@@ -68,10 +74,12 @@ def measured_traffic(workload: str, which: str):
     if tab.get("source_sha256") != sha or workload not in tab:
         return None
     t = tab[workload][which]
-    return {"read_bytes": t["read_bytes"], "write_bytes": t["write_bytes"], "bytes": t["read_bytes"] + t["write_bytes"]}
+    return {"read_bytes": t["read_bytes"], "write_bytes": t["write_bytes"], "bytes": t["read_bytes"] + t["write_bytes"],
+            "source": "replayed, not measured by this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run "
+                      f"(summary under profiles/, {tab.get('profile', 'ffn_hbm_traffic')}); valid for ffn.hip sha256 {sha[:12]}"}
 
 
-def cpu_baseline(wl, counts, offsets, perm):
+def cpu_baseline(wl, counts):
     """The oracle as it stands, timed on the host cores on a bounded sample: routing and batching of
     the whole batch, then the expert FFN of the first experts' complete segments until about
     15 s of CPU work is spent (the combine, a scaled row copy, is left out of the sample).  tokens/s = sampled assignments / (their FFN time + the
@@ -119,6 +127,102 @@ def cpu_baseline(wl, counts, offsets, perm):
                       f"{experts} complete expert segments = {done} assignments ({t_ffn:.2f} s)"}
 
 
+def streamed_leg(M, torch, np, cfg, x, gate, bias, host_packed, y, ws, wl, steps, warmup, n_slots, order="ascending",
+                 keep=False, tokens_per_load=None):
+    """Host-streamed steps of the layer (Section 6.2: experts in pinned host memory, loaded on a copy stream
+    while earlier experts compute): per-step time, host-to-device rate over the copy window, and how much of
+    the shorter of (the same copies alone, the same layer with resident experts) the streamed step hides."""
+    eb = M.moe_expert_bytes(cfg)
+    slots = torch.empty((n_slots, eb), dtype=torch.uint8, device="cuda")
+    ctx = M.StreamCtx(cfg, host_packed, slots, n_slots)
+    if keep:
+        ctx.keep_experts(True)
+    if order == "greedy":
+        # Section 6.2 takes alpha and beta from the peak rates of the machine
+        tpl = tokens_per_load or (eb / 64e9) / (6.0 * wl.d * wl.f / (MFMA_BF16_PEAK_TFLOPS * 1e12))
+        ctx.set_order(M.ORDER_GREEDY, tpl, n_slots)
+
+    def step():
+        M.moe_layer_forward(cfg, x, gate, bias, None, ctx, y, ws)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    copy_ms, copy_bytes, loaded = [], 0, []
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+        st = ctx.stats()                         # per-call copy figures; the wait is part of the streamed step anyway
+        copy_ms.append(st["copy_ms"])
+        copy_bytes = st["bytes"]
+        loaded.append(st["n_loaded"])
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    cm = float(np.mean(copy_ms))
+    h2d = copy_bytes / (cm * 1e-3) / 1e9 if cm > 0 else 0.0
+    roof = {"bound": "h2d", "achieved": h2d, "peak": 64.0, "unit": "GB/s", "frac": h2d / 64.0, "traffic": None,
+            "kernel": "hipMemcpyAsync pinned host -> HBM slot (copy stream)", "avg_copy_window_ms": cm,
+            "bytes_per_step": copy_bytes, "note": "peak = PCIe Gen5 x16 raw, one direction"}
+    rec = {"workload": wl.name, "T": wl.T, "slots": n_slots, "order": order, "steps": steps, "warmup": warmup,
+           "tokens_per_s": wl.T / (ms_per_step * 1e-3), "h2d_gbs": h2d, "h2d_frac_of_64_gbs": h2d / 64.0,
+           "copy_window_ms": cm, "step_ms": ms_per_step, "copy_share_of_step": cm / ms_per_step if ms_per_step > 0 else 0.0,
+           "experts_loaded_per_step": float(np.mean(loaded))}
+    counts = torch.empty(cfg.E, dtype=torch.int32, device="cuda")
+    idx = torch.empty((wl.T, wl.k), dtype=torch.int32, device="cuda")
+    w = torch.empty((wl.T, wl.k), dtype=torch.float32, device="cuda")
+    offsets = torch.empty(cfg.E + 1, dtype=torch.int32, device="cuda")
+    perm = torch.empty(wl.A, dtype=torch.int32, device="cuda")
+    inv = torch.empty(wl.A, dtype=torch.int32, device="cuda")
+    M.moe_route(cfg, x, gate, bias, idx, w, ws)
+    M.moe_permute(cfg, x, idx, counts, offsets, perm, inv, None, ws)
+    torch.cuda.synchronize()
+    live_experts = [int(e) for e in np.nonzero(counts.cpu().numpy())[0]]
+    if not keep:
+        # Overlap of loading and computing (Section 6.2: separate streams so that the two run side by side):
+        # the same copies alone (back to back on a side stream, nothing else running), the same layer alone
+        # (experts resident), and how much of the shorter of the two the streamed step hides.
+        side = torch.cuda.Stream()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        alone_ms = []
+        for _ in range(3):
+            torch.cuda.synchronize()
+            with torch.cuda.stream(side):
+                ev0.record(side)
+                for i, e in enumerate(live_experts):
+                    slots[i % n_slots].copy_(host_packed[e], non_blocking=True)
+                ev1.record(side)
+            ev1.synchronize()
+            alone_ms.append(ev0.elapsed_time(ev1))
+        copy_alone_ms = float(np.mean(alone_ms[1:]))
+        resident = torch.empty((cfg.E, eb), dtype=torch.uint8, device="cuda")
+        resident.copy_(host_packed)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            M.moe_layer_forward(cfg, x, gate, bias, resident, None, y, ws)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(10):
+            M.moe_layer_forward(cfg, x, gate, bias, resident, None, y, ws)
+        torch.cuda.synchronize()
+        compute_alone_ms = (time.perf_counter() - t1) * 1e3 / 10
+        del resident
+        shorter = min(copy_alone_ms, compute_alone_ms)
+        copy_alone_gbs = len(live_experts) * eb / (copy_alone_ms * 1e-3) / 1e9
+        rec.update({
+            "copy_alone_ms": copy_alone_ms, "copy_alone_gbs": copy_alone_gbs, "compute_alone_ms": compute_alone_ms,
+            "exposed_ms": ms_per_step - max(copy_alone_ms, compute_alone_ms),
+            "overlap": (copy_alone_ms + compute_alone_ms - ms_per_step) / shorter,
+            "overlap_note": "(copies alone + layer alone - streamed step) / the shorter of the two; 1 = the shorter one is "
+                            "hidden completely; exposed_ms = streamed step - the longer of the two",
+            "h2d_frac_of_copies_alone": h2d / copy_alone_gbs})
+    if order == "greedy":
+        o, ok = ctx.last_order()
+        rec.update({"order_first": o[:8], "order_last": o[-4:], "constraints_satisfiable": ok})
+    ctx.close()
+    del slots
+    return ms_per_step, roof, rec, counts.cpu().numpy()
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -152,92 +256,92 @@ def main():
         args.warmup = 5 if wl.streamed else 30
     if args.steps < 1 or args.warmup < 0:
         sys.exit("bench.py: --steps must be positive and --warmup not negative")
+    # the default run (the layer the metric is quoted on, experts resident) also runs a short streamed leg on the
+    # same weights, which needs them in pinned host memory as well
+    streaming_leg = (not wl.streamed and args.workload == "c3" and args.tokens is None and not args.no_streaming_leg)
     t_setup = time.perf_counter()
-    L = H.build_layer(wl, resident=not wl.streamed, host_copy=wl.streamed)
+    L = H.build_layer(wl, resident=not wl.streamed, host_copy=wl.streamed or streaming_leg)
+    # the gate is frozen (Section 2.3): packed once, like the experts
+    gate = torch.empty(M.moe_gate_bytes(L.cfg), dtype=torch.uint8, device="cuda")
+    M.moe_pack_gate(L.cfg, L.Wg, gate)
+    cfg = L.cfg.with_packed_gate()
+    torch.cuda.synchronize()
     print(f"[bench] {wl.name}: inputs resident after {time.perf_counter() - t_setup:.1f} s", file=sys.stderr, flush=True)
-    eb = M.moe_expert_bytes(L.cfg)
-    ctx = None
-    if wl.streamed:
-        slots = torch.empty((args.slots, eb), dtype=torch.uint8, device="cuda")
-        ctx = M.StreamCtx(L.cfg, L.host_packed, slots, args.slots)
-        if args.keep_experts:
-            ctx.keep_experts(True)
-        if args.order == "greedy":
-            # Section 6.2 takes alpha and beta from the peak rates of the machine
-            tpl = args.tokens_per_load or (eb / 64e9) / (6.0 * wl.d * wl.f / (MFMA_BF16_PEAK_TFLOPS * 1e12))
-            ctx.set_order(M.ORDER_GREEDY, tpl, args.slots)
-
-    def step():
-        M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, ctx, L.y, L.ws)
-
-    if args.calibrate_copy:
-        src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    if not wl.streamed:
-        # two events around the dominant kernel in every tenth step, every third in short runs (each event costs
-        # the step some 7 us of idle time between two kernels)
-        every = 10 if args.steps >= 100 else 3
-        M.moe_up_kernel_timing_enable((args.steps + every - 1) // every, every)
-    copy_ms, copy_bytes, loaded = [], 0, []
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-        if wl.streamed:                          # per-call copy figures; the wait is part of the streamed step anyway
-            st = ctx.stats()
-            copy_ms.append(st["copy_ms"])
-            copy_bytes = st["bytes"]
-            loaded.append(st["n_loaded"])
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
-    tokens_per_s = wl.T / (ms_per_step * 1e-3)
-    if not wl.streamed:
-        up_samples = M.moe_up_kernel_timing_read(args.steps)
-        up_ms = float(np.mean(up_samples))
-        # per-stage breakdown from extra steps outside the timed region (events between all stages cost
-        # a few microseconds of idle time each, which the timed steps do not pay)
-        n_extra = min(args.steps, 10)
-        M.moe_stage_timing_enable(n_extra)
-        for _ in range(n_extra):
-            step()
-        torch.cuda.synchronize()
-        per_call = M.moe_stage_timing_read(n_extra)
-        M.moe_stage_timing_disable()
-
-    # what the run did, read back from the workspace of the last step
-    lay_counts = torch.empty(wl.E, dtype=torch.int32, device="cuda")
-    idx = torch.empty((wl.T, wl.k), dtype=torch.int32, device="cuda")
-    w = torch.empty((wl.T, wl.k), dtype=torch.float32, device="cuda")
-    offsets = torch.empty(wl.E + 1, dtype=torch.int32, device="cuda")
-    perm = torch.empty(wl.A, dtype=torch.int32, device="cuda")
-    inv = torch.empty(wl.A, dtype=torch.int32, device="cuda")
-    M.moe_route(L.cfg, L.x, L.Wg, L.bias, idx, w, L.ws)
-    M.moe_permute(L.cfg, L.x, idx, lay_counts, offsets, perm, inv, None, L.ws)
-    torch.cuda.synchronize()
-    counts = lay_counts.cpu().numpy()
-    live = int((counts > 0).sum())
     A, d, f, es = wl.A, wl.d, wl.f, 2 if wl.dtype == "bf16" else 4
 
     out = {
         "metric": "MoE-FFN tokens/s (d4096,ff10240,E32,bf16)" if args.workload in ("c3", "c4a", "c4b")
                   else f"MoE-FFN tokens/s (d{d},ff{f},E{wl.E},{wl.dtype})",
-        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": None, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": wl.name, "T": wl.T, "d_model": d, "d_ff": f, "experts": wl.E, "top_k": wl.k,
-                   "mode": f"host-streamed experts (K={args.slots} slots, {args.order} order"
-                           f"{', experts kept between steps' if args.keep_experts else ''})" if wl.streamed
-                           else "experts resident in HBM",
-                   "non_empty_experts": live, "max_tokens_per_expert": int(counts.max()),
-                   "min_tokens_per_expert": int(counts.min())},
     }
+
+    if wl.streamed:
+        ms_per_step, roof, rec, counts = streamed_leg(M, torch, np, cfg, L.x, gate, L.bias, L.host_packed, L.y, L.ws, wl,
+                                                      args.steps, args.warmup, args.slots, args.order, args.keep_experts,
+                                                      args.tokens_per_load)
+        out["roofline"] = roof
+        out["streaming"] = rec
+    else:
+        def step():
+            M.moe_layer_forward(cfg, L.x, gate, L.bias, L.packed, None, L.y, L.ws)
+
+        if args.calibrate_copy:
+            src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+            dst = torch.empty_like(src)
+            torch.cuda.synchronize()
+            dst.copy_(src)
+            torch.cuda.synchronize()
+            del src, dst
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        # two events around the dominant kernel in every tenth step, every third in short runs (each event costs
+        # the step some 7 us of idle time between two kernels): those steps go through the timed entry point
+        every = 10 if args.steps >= 100 else 3
+        up_timer = M.Timer((args.steps + every - 1) // every, M.TIME_UP_KERNEL)
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            if i % every == 0:
+                M.moe_layer_forward_timed(cfg, L.x, gate, L.bias, L.packed, L.y, L.ws, up_timer)
+            else:
+                step()
+        torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+        up_samples = up_timer.read()
+        up_timer.close()
+        up_ms = float(np.mean(up_samples))
+        # per-stage breakdown from extra steps outside the timed region (events between all stages cost
+        # a few microseconds of idle time each, which the timed steps do not pay)
+        n_extra = min(args.steps, 10)
+        stage_timer = M.Timer(n_extra, M.TIME_STAGES)
+        for _ in range(n_extra):
+            M.moe_layer_forward_timed(cfg, L.x, gate, L.bias, L.packed, L.y, L.ws, stage_timer)
+        torch.cuda.synchronize()
+        per_call = stage_timer.read()
+        stage_timer.close()
+        # what the run did, read back through the staged calls
+        lay_counts = torch.empty(wl.E, dtype=torch.int32, device="cuda")
+        idx = torch.empty((wl.T, wl.k), dtype=torch.int32, device="cuda")
+        w = torch.empty((wl.T, wl.k), dtype=torch.float32, device="cuda")
+        offsets = torch.empty(wl.E + 1, dtype=torch.int32, device="cuda")
+        perm = torch.empty(wl.A, dtype=torch.int32, device="cuda")
+        inv = torch.empty(wl.A, dtype=torch.int32, device="cuda")
+        M.moe_route(cfg, L.x, gate, L.bias, idx, w, L.ws)
+        M.moe_permute(cfg, L.x, idx, lay_counts, offsets, perm, inv, None, L.ws)
+        torch.cuda.synchronize()
+        counts = lay_counts.cpu().numpy()
+    live = int((counts > 0).sum())
+    out["value"] = wl.T / (ms_per_step * 1e-3)
+    out["ms_per_step"] = ms_per_step
+    out["config"] = {"workload": wl.name, "T": wl.T, "d_model": d, "d_ff": f, "experts": wl.E, "top_k": wl.k,
+                     "mode": f"host-streamed experts (K={args.slots} slots, {args.order} order"
+                             f"{', experts kept between steps' if args.keep_experts else ''})" if wl.streamed
+                             else "experts resident in HBM",
+                     "gate": "packed once (moe_pack_gate)",
+                     "non_empty_experts": live, "max_tokens_per_expert": int(counts.max()),
+                     "min_tokens_per_expert": int(counts.min())}
     ffn_flops = 6.0 * d * f * A
     if not wl.streamed:
         stage_ms = {s: float(np.mean([c[s] for c in per_call])) for s in M.STAGES}
@@ -270,62 +374,38 @@ def main():
                       "mfma_frac": ffn_flops / (ffn_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                       "weight_gbs": live * 3 * d * f * es / (ffn_ms * 1e-3) / 1e9,
                       "down_gbs": down_bytes / (stage_ms["ffn_down"] * 1e-3) / 1e9}
-    else:
-        cm = float(np.mean(copy_ms))
-        h2d = copy_bytes / (cm * 1e-3) / 1e9 if cm > 0 else 0.0
-        out["roofline"] = {"bound": "h2d", "achieved": h2d, "peak": 64.0, "unit": "GB/s", "frac": h2d / 64.0,
-                           "traffic": None, "kernel": "hipMemcpyAsync pinned host -> HBM slot (copy stream)",
-                           "avg_copy_window_ms": cm, "bytes_per_step": copy_bytes,
-                           "note": "peak = PCIe Gen5 x16 raw, one direction"}
-        out["streaming"] = {"h2d_gbs": h2d, "copy_window_ms": cm, "step_ms": ms_per_step,
-                            "copy_share_of_step": cm / ms_per_step,
-                            "experts_loaded_per_step": float(np.mean(loaded))}
-        if not args.keep_experts:
-            # Overlap of loading and computing (Section 6.2: separate streams so that the two run side by
-            # side): the same copies alone (back to back on a side stream, nothing else running), the same
-            # layer alone (experts resident), and how much of the shorter of the two the streamed step hides.
-            live_experts = [int(e) for e in np.nonzero(counts)[0]]
-            side = torch.cuda.Stream()
-            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            alone_ms = []
-            for _ in range(3):
-                torch.cuda.synchronize()
-                with torch.cuda.stream(side):
-                    ev0.record(side)
-                    for i, e in enumerate(live_experts):
-                        slots[i % args.slots].copy_(L.host_packed[e], non_blocking=True)
-                    ev1.record(side)
-                ev1.synchronize()
-                alone_ms.append(ev0.elapsed_time(ev1))
-            copy_alone_ms = float(np.mean(alone_ms[1:]))
-            resident = torch.empty((wl.E, eb), dtype=torch.uint8, device="cuda")
-            resident.copy_(L.host_packed)
+        if not args.no_graph:
+            # the same step recorded once into a HIP graph (kernel launches only) and replayed
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                step()
             torch.cuda.synchronize()
-            for _ in range(3):
-                M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, resident, None, L.y, L.ws)
+            for _ in range(min(args.warmup, 10)):
+                g.replay()
             torch.cuda.synchronize()
             t1 = time.perf_counter()
-            for _ in range(10):
-                M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, resident, None, L.y, L.ws)
+            for _ in range(args.steps):
+                g.replay()
             torch.cuda.synchronize()
-            compute_alone_ms = (time.perf_counter() - t1) * 1e3 / 10
-            del resident
-            shorter = min(copy_alone_ms, compute_alone_ms)
-            out["streaming"].update({
-                "copy_alone_ms": copy_alone_ms, "copy_alone_gbs": len(live_experts) * eb / (copy_alone_ms * 1e-3) / 1e9,
-                "compute_alone_ms": compute_alone_ms,
-                "exposed_ms": ms_per_step - copy_alone_ms,
-                "overlap": (copy_alone_ms + compute_alone_ms - ms_per_step) / shorter,
-                "overlap_note": "(copies alone + layer alone - streamed step) / the shorter of the two; 1 = the shorter one is hidden "
-                                "completely; the streamed step also holds the routing that must precede the first load",
-                "h2d_frac_of_copies_alone": h2d / (len(live_experts) * eb / (copy_alone_ms * 1e-3) / 1e9)})
-        if args.order == "greedy":
-            order, ok = ctx.last_order()
-            out["streaming"].update({"order_first": order[:8], "order_last": order[-4:], "constraints_satisfiable": ok})
+            g_ms = (time.perf_counter() - t1) * 1e3 / args.steps
+            out["graph"] = {"ms_per_step": g_ms, "tokens_per_s": wl.T / (g_ms * 1e-3), "steps": args.steps,
+                            "note": "the same layer call captured once in a HIP graph and replayed; value/ms_per_step above "
+                                    "are the eager launches"}
+            del g
+        if streaming_leg:
+            # the other half of the metric: the same layer and weights with host-streamed experts, on the short batch
+            # of the streamed configuration (T 512); a few steps are enough, every step moves all 32 experts
+            wls = W.CONFIGS["c4a"]
+            cfgs = H.cfg_of(wls).with_packed_gate()
+            xs = H.to_device(W.gen_x(wls), wls.dtype)
+            wss = torch.empty(M.moe_workspace_bytes(cfgs), dtype=torch.uint8, device="cuda")
+            ys = torch.empty((wls.T, wls.d), dtype=cfgs.torch_dtype, device="cuda")
+            _, sroof, srec, _ = streamed_leg(M, torch, np, cfgs, xs, gate, None, L.host_packed, ys, wss, wls, 5, 2,
+                                             args.slots)
+            srec["roofline"] = sroof
+            out["streaming"] = srec
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, counts, offsets.cpu().numpy(), perm.cpu().numpy())
-    if ctx is not None:
-        ctx.close()
+        out["cpu_baseline"] = cpu_baseline(wl, counts)
     print(json.dumps(out))
 
 

@@ -18,12 +18,17 @@ class MoeError(RuntimeError):
 
 class MoeCfg(C.Structure):
     _fields_ = [("T", C.c_int32), ("d", C.c_int32), ("f", C.c_int32), ("E", C.c_int32), ("k", C.c_int32),
-                ("dtype", C.c_int32), ("renorm", C.c_int32), ("act", C.c_int32), ("gate", C.c_int32)]
+                ("dtype", C.c_int32), ("renorm", C.c_int32), ("act", C.c_int32), ("gate", C.c_int32),
+                ("gate_packed", C.c_int32)]
 
     @classmethod
-    def make(cls, T, d, f, E, k=1, dtype="bf16", renorm=1, act=0, gate=0) -> "MoeCfg":
+    def make(cls, T, d, f, E, k=1, dtype="bf16", renorm=1, act=0, gate=0, gate_packed=0) -> "MoeCfg":
         code = {"bf16": MOE_BF16, "f32": MOE_F32}[dtype] if isinstance(dtype, str) else int(dtype)
-        return cls(T, d, f, E, k, code, renorm, act, gate)
+        return cls(T, d, f, E, k, code, renorm, act, gate, gate_packed)
+
+    def with_packed_gate(self, on: bool = True) -> "MoeCfg":
+        """A copy of this cfg whose W_g arguments are (or are not) the block written by moe_pack_gate."""
+        return MoeCfg(self.T, self.d, self.f, self.E, self.k, self.dtype, self.renorm, self.act, self.gate, 1 if on else 0)
 
     @property
     def torch_dtype(self):
@@ -50,6 +55,8 @@ def lib() -> C.CDLL:
             "moe_workspace_bytes": [cfgp, C.POINTER(C.c_size_t)],
             "moe_expert_bytes": [cfgp, C.POINTER(C.c_size_t)],
             "moe_pack_weights": [cfgp, p, p, p, p, p],
+            "moe_gate_bytes": [cfgp, C.POINTER(C.c_size_t)],
+            "moe_pack_gate": [cfgp, p, p, p],
             "moe_route": [cfgp, p, p, f32p, i32p, f32p, p, p],
             "moe_permute": [cfgp, p, i32p, i32p, i32p, i32p, i32p, p, p, p],
             "moe_expert_ffn": [cfgp, p, i32p, p, p, p, p],
@@ -67,12 +74,11 @@ def lib() -> C.CDLL:
             "moe_stream_ctx_prefetch": [p, C.c_int32],
             "moe_plan_slots": [C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int64),
                                C.POINTER(C.c_int64), C.POINTER(C.c_int32), C.POINTER(C.c_int32)],
-            "moe_stage_timing_enable": [C.c_int32],
-            "moe_stage_timing_read": [C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)],
-            "moe_stage_timing_disable": [],
-            "moe_up_kernel_timing_enable": [C.c_int32],
-            "moe_up_kernel_timing_every": [C.c_int32],
-            "moe_up_kernel_timing_read": [C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)],
+            "moe_timer_create": [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)],
+            "moe_timer_destroy": [p],
+            "moe_timer_reset": [p],
+            "moe_timer_read": [p, C.POINTER(C.c_float), C.c_int32, C.POINTER(C.c_int32)],
+            "moe_layer_forward_timed": [cfgp, p, p, f32p, p, p, p, p, p],
         }
         for name, args in sigs.items():
             fn = getattr(L, name)
@@ -115,6 +121,16 @@ def moe_expert_bytes(cfg: MoeCfg) -> int:
 def moe_pack_weights(cfg, W_in_e, W_gate_e, W_out_e, packed_e, stream=None) -> None:
     _check(lib().moe_pack_weights(C.byref(cfg), _ptr(W_in_e), _ptr(W_gate_e), _ptr(W_out_e), _ptr(packed_e),
                                   _stream(stream)))
+
+
+def moe_gate_bytes(cfg: MoeCfg) -> int:
+    n = C.c_size_t(0)
+    _check(lib().moe_gate_bytes(C.byref(cfg), C.byref(n)))
+    return n.value
+
+
+def moe_pack_gate(cfg, W_g, gate_packed, stream=None) -> None:
+    _check(lib().moe_pack_gate(C.byref(cfg), _ptr(W_g), _ptr(gate_packed), _stream(stream)))
 
 
 def moe_route(cfg, x, W_g, gate_bias, idx, w, ws, stream=None) -> None:
@@ -221,34 +237,49 @@ def moe_stream_slots_that_fit(cfg: MoeCfg, reserve_bytes: int = 0) -> int:
 
 
 STAGES = ("route", "permute", "ffn_up", "ffn_down", "combine")
+TIME_STAGES, TIME_UP_KERNEL = 0, 1
 
 
-def moe_stage_timing_enable(max_calls: int) -> None:
-    _check(lib().moe_stage_timing_enable(max_calls))
+class Timer:
+    """Event timing of resident layer calls (moe_timer_* of the library): all five stages, or the expert
+    up-projection kernel alone."""
+
+    def __init__(self, max_calls: int, mode: int = TIME_STAGES):
+        self._h = C.c_void_p(None)
+        self.mode = mode
+        self.max_calls = max_calls
+        _check(lib().moe_timer_create(max_calls, mode, C.byref(self._h)))
+
+    @property
+    def handle(self):
+        return self._h
+
+    def reset(self) -> None:
+        _check(lib().moe_timer_reset(self._h))
+
+    def read(self):
+        """Per recorded call: {stage: ms} (all stages) or the kernel's ms (up-projection kernel alone)."""
+        width = len(STAGES) if self.mode == TIME_STAGES else 1
+        buf = (C.c_float * (self.max_calls * width))()
+        n = C.c_int32(0)
+        _check(lib().moe_timer_read(self._h, buf, self.max_calls, C.byref(n)))
+        got = min(n.value, self.max_calls)
+        if self.mode == TIME_STAGES:
+            return [{s: buf[c * width + i] for i, s in enumerate(STAGES)} for c in range(got)]
+        return [buf[c] for c in range(got)]
+
+    def close(self) -> None:
+        if self._h:
+            lib().moe_timer_destroy(self._h)
+            self._h = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
-def moe_stage_timing_read(max_calls: int):
-    """List of per-call dicts {stage: ms}."""
-    buf = (C.c_float * (max_calls * len(STAGES)))()
-    n = C.c_int32(0)
-    _check(lib().moe_stage_timing_read(buf, max_calls, C.byref(n)))
-    got = min(n.value, max_calls)
-    return [{s: buf[c * len(STAGES) + i] for i, s in enumerate(STAGES)} for c in range(got)]
-
-
-def moe_up_kernel_timing_enable(max_calls: int, every: int = 1) -> None:
-    _check(lib().moe_up_kernel_timing_enable(max_calls))
-    if every != 1:
-        _check(lib().moe_up_kernel_timing_every(every))
-
-
-def moe_up_kernel_timing_read(max_calls: int):
-    """List of per-call durations of the expert up-projection kernel in ms."""
-    buf = (C.c_float * max_calls)()
-    n = C.c_int32(0)
-    _check(lib().moe_up_kernel_timing_read(buf, max_calls, C.byref(n)))
-    return [buf[c] for c in range(min(n.value, max_calls))]
-
-
-def moe_stage_timing_disable() -> None:
-    _check(lib().moe_stage_timing_disable())
+def moe_layer_forward_timed(cfg, x, W_g, gate_bias, W_packed, y, ws, timer: Timer, stream=None) -> None:
+    _check(lib().moe_layer_forward_timed(C.byref(cfg), _ptr(x), _ptr(W_g), _ptr(gate_bias), _ptr(W_packed), _ptr(y),
+                                         _ptr(ws), _stream(stream), timer.handle))

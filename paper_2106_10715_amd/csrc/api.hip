@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "common.h"
@@ -23,6 +24,26 @@ int fail(int code, const char* fmt, ...) {
 
 void clear_error() { g_err[0] = '\0'; }
 
+int device_info(int* device, const DeviceInfo** info) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex lock;
+    static DeviceInfo table[kMaxDevices];
+    static bool known[kMaxDevices] = {};
+    int dev = 0;
+    MOE_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(MOE_ERR_UNSUPPORTED, "device %d: only devices 0..%d are supported", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> guard(lock);
+    if (!known[dev]) {
+        int n = 0;
+        MOE_HIP_CHECK(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
+        table[dev].compute_units = n > 0 ? n : 256;
+        known[dev] = true;
+    }
+    *device = dev;
+    *info = &table[dev];
+    return MOE_OK;
+}
+
 int check_cfg(const moe_cfg* c) {
     if (c == nullptr) return fail(MOE_ERR_INVALID_ARG, "cfg is NULL");
     if (c->dtype != MOE_F32 && c->dtype != MOE_BF16) return fail(MOE_ERR_INVALID_ARG, "dtype must be MOE_F32 or MOE_BF16");
@@ -36,6 +57,7 @@ int check_cfg(const moe_cfg* c) {
     if (c->gate != MOE_GATE_TOPK && c->gate != MOE_GATE_HASH) return fail(MOE_ERR_INVALID_ARG, "gate must be MOE_GATE_TOPK or MOE_GATE_HASH");
     if (c->gate == MOE_GATE_HASH && (c->E < 2 || (c->E & (c->E - 1)) != 0 || c->k != 1))
         return fail(MOE_ERR_INVALID_ARG, "the hashing gate needs E a power of two >= 2 and k = 1 (got E = %d, k = %d)", c->E, c->k);
+    if (c->gate_packed != 0 && c->gate_packed != 1) return fail(MOE_ERR_INVALID_ARG, "gate_packed must be 0 or 1");
     const long long A = static_cast<long long>(c->T) * c->k;
     const long long widest = c->d > c->f ? c->d : c->f;
     if (A * widest >= (1LL << 31)) return fail(MOE_ERR_INVALID_ARG, "T*k*max(d,f) must stay below 2^31");
@@ -97,17 +119,13 @@ struct moe_stream_ctx {
     int32_t order[256];
 };
 
-// Optional per-stage event timing of resident moe_layer_forward calls (measurement aid).
-namespace {
+// Event timing of resident layer calls (measurement aid): the caller's object, filled by moe_layer_forward_timed.
 constexpr int kStageEvents = 6;   // before route, after route, permute, up, down, combine
-struct StageTimer {
-    bool on = false;
-    bool up_only = false;         // only the two events around the up-projection kernel
+struct moe_timer {
+    int mode = MOE_TIME_STAGES;
     int cap = 0, n = 0;
-    int every = 1, seen = 0;      // calls seen since enabling; the calls 0, every, 2 every, ... are timed
-    hipEvent_t* ev = nullptr;
-} g_timer;
-}  // namespace
+    hipEvent_t* ev = nullptr;     // [cap][kStageEvents]
+};
 
 #define REQUIRE(ptr, name) \
     if ((ptr) == nullptr) return fail(MOE_ERR_INVALID_ARG, "%s is NULL", name)
@@ -141,10 +159,26 @@ int moe_pack_weights(const moe_cfg* cfg, const void* W_in_e, const void* W_gate_
     return launch_pack(*cfg, W_in_e, W_gate_e, W_out_e, packed_e, static_cast<hipStream_t>(stream));
 }
 
+int moe_gate_bytes(const moe_cfg* cfg, size_t* bytes) {
+    if (int rc = check_cfg(cfg)) return rc;
+    REQUIRE(bytes, "bytes");
+    *bytes = gate_packed_bytes(*cfg);
+    return MOE_OK;
+}
+
+int moe_pack_gate(const moe_cfg* cfg, const void* W_g, void* gate_packed, void* stream) {
+    if (int rc = check_cfg(cfg)) return rc;
+    REQUIRE(W_g, "W_g"); REQUIRE(gate_packed, "gate_packed");
+    REQUIRE_ALIGNED(W_g, "W_g");
+    if ((reinterpret_cast<uintptr_t>(gate_packed) & 255) != 0) return fail(MOE_ERR_INVALID_ARG, "gate_packed must be 256-byte aligned");
+    return launch_pack_gate(*cfg, W_g, gate_packed, static_cast<hipStream_t>(stream));
+}
+
 int moe_route(const moe_cfg* cfg, const void* x, const void* W_g, const float* gate_bias, int32_t* idx, float* w,
               void* ws, void* stream) {
     if (int rc = check_cfg(cfg)) return rc;
     REQUIRE(W_g, "W_g");
+    if (cfg->gate_packed) REQUIRE_ALIGNED(W_g, "W_g (packed gate)");
     if (cfg->T == 0) return MOE_OK;
     REQUIRE(x, "x"); REQUIRE(idx, "idx"); REQUIRE(w, "w"); REQUIRE(ws, "ws");
     REQUIRE_ALIGNED(x, "x"); REQUIRE_ALIGNED(ws, "ws");
@@ -191,10 +225,27 @@ int moe_combine(const moe_cfg* cfg, const void* Yp, const int32_t* inv, const fl
     return launch_combine(*cfg, Yp, inv, w, y, static_cast<hipStream_t>(stream));
 }
 
-int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const float* gate_bias,
-                      const void* W_packed, moe_stream_ctx* sctx, void* y, void* ws, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// Forgets what the slots of a streamed context hold unless the call that planned them got all its copies
+// enqueued: a slot marked as holding an expert whose copy was never issued would be computed from as it is.
+struct SlotGuard {
+    moe_stream_ctx* ctx;
+    bool ok = false;
+    ~SlotGuard() {
+        if (ctx != nullptr && !ok)
+            for (int i = 0; i < kMaxSlots; ++i) ctx->slot_expert[i] = -1;
+    }
+};
+
+// The layer; `timer` (resident mode only) receives this call's events if it has room.
+int layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const float* gate_bias, const void* W_packed,
+                  moe_stream_ctx* sctx, void* y, void* ws, void* stream, moe_timer* timer) {
     if (int rc = check_cfg(cfg)) return rc;
     REQUIRE(W_g, "W_g");
+    if (cfg->gate_packed) REQUIRE_ALIGNED(W_g, "W_g (packed gate)");
     if (sctx == nullptr) { REQUIRE(W_packed, "W_packed (resident mode)"); REQUIRE_ALIGNED(W_packed, "W_packed"); }
     if (sctx != nullptr &&
         (sctx->cfg.d != cfg->d || sctx->cfg.f != cfg->f || sctx->cfg.E != cfg->E || sctx->cfg.dtype != cfg->dtype))
@@ -228,10 +279,10 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
     void* ffn_out = direct ? y : static_cast<void*>(base + L.Yp);
     const int32_t* row_map = direct ? perm : nullptr;
 
-    hipEvent_t* tev = nullptr;     // this call's stage events, if stage timing is on and has room
-    if (sctx == nullptr && g_timer.on && g_timer.n < g_timer.cap && g_timer.seen++ % g_timer.every == 0)
-        tev = g_timer.ev + kStageEvents * g_timer.n++;
-    const bool all_stages = tev != nullptr && !g_timer.up_only;
+    hipEvent_t* tev = nullptr;     // this call's events, if it is timed and the timer has room
+    if (timer != nullptr && timer->n < timer->cap) tev = timer->ev + kStageEvents * timer->n++;
+    const bool up_only = timer != nullptr && timer->mode == MOE_TIME_UP_KERNEL;
+    const bool all_stages = tev != nullptr && !up_only;
     if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[0], s));
     if (int rc = launch_route(c, x, W_g, gate_bias, idx, w, base + L.route, s)) return rc;
     if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[1], s));
@@ -246,10 +297,11 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
     if (sctx == nullptr) {
         if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, 0, c.E, W_packed, eb, A, base + L.H, ffn_out,
                                        reinterpret_cast<int32_t*>(base + L.ffn_plan), s, tev ? tev[3] : nullptr,
-                                       tev && g_timer.up_only ? tev[2] : nullptr, row_map, planned))
+                                       tev && up_only ? tev[2] : nullptr, row_map, planned))
             return rc;
         if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[4], s));
     } else {
+        SlotGuard guard{sctx};
         // The host has to know which experts hold tokens (and how many) before it can queue loads.
         MOE_HIP_CHECK(hipMemcpyAsync(sctx->h_counts, counts, sizeof(int32_t) * c.E, hipMemcpyDeviceToHost, s));
         MOE_HIP_CHECK(hipStreamSynchronize(s));
@@ -329,6 +381,7 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
             sctx->n_loaded = i;
             sctx->timed = i > 0;
         }
+        guard.ok = true;
     }
     if (!direct)
         if (int rc = launch_combine(c, base + L.Yp, inv, w, y, s)) return rc;
@@ -336,75 +389,76 @@ int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const 
     return MOE_OK;
 }
 
-int moe_stage_timing_enable(int32_t max_calls) {
+}  // namespace
+
+extern "C" {
+
+int moe_layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const float* gate_bias,
+                      const void* W_packed, moe_stream_ctx* sctx, void* y, void* ws, void* stream) {
+    return layer_forward(cfg, x, W_g, gate_bias, W_packed, sctx, y, ws, stream, nullptr);
+}
+
+int moe_layer_forward_timed(const moe_cfg* cfg, const void* x, const void* W_g, const float* gate_bias,
+                            const void* W_packed, void* y, void* ws, void* stream, moe_timer* timer) {
+    REQUIRE(timer, "timer");
+    return layer_forward(cfg, x, W_g, gate_bias, W_packed, nullptr, y, ws, stream, timer);
+}
+
+int moe_timer_create(int32_t max_calls, int32_t mode, moe_timer** out) {
+    REQUIRE(out, "out");
+    *out = nullptr;
     if (max_calls < 1 || max_calls > 4096) return fail(MOE_ERR_INVALID_ARG, "max_calls must be in [1, 4096]");
-    moe_stage_timing_disable();
-    g_timer.ev = new (std::nothrow) hipEvent_t[static_cast<size_t>(max_calls) * kStageEvents]();
-    if (g_timer.ev == nullptr) return fail(MOE_ERR_HIP, "out of host memory");
-    g_timer.cap = max_calls;
+    if (mode != MOE_TIME_STAGES && mode != MOE_TIME_UP_KERNEL) return fail(MOE_ERR_INVALID_ARG, "unknown timer mode %d", mode);
+    moe_timer* t = new (std::nothrow) moe_timer();
+    if (t == nullptr) return fail(MOE_ERR_HIP, "out of host memory");
+    t->mode = mode;
+    t->ev = new (std::nothrow) hipEvent_t[static_cast<size_t>(max_calls) * kStageEvents]();
+    if (t->ev == nullptr) { delete t; return fail(MOE_ERR_HIP, "out of host memory"); }
+    t->cap = max_calls;
     for (int i = 0; i < max_calls * kStageEvents; ++i) {
-        const hipError_t e = hipEventCreate(&g_timer.ev[i]);
+        const hipError_t e = hipEventCreate(&t->ev[i]);
         if (e != hipSuccess) {
-            g_timer.cap = i / kStageEvents;
-            moe_stage_timing_disable();
+            moe_timer_destroy(t);
             return fail(MOE_ERR_HIP, "hipEventCreate failed: %s", hipGetErrorString(e));
         }
     }
-    g_timer.n = 0;
-    g_timer.on = true;
+    *out = t;
     return MOE_OK;
 }
 
-int moe_up_kernel_timing_enable(int32_t max_calls) {
-    if (int rc = moe_stage_timing_enable(max_calls)) return rc;
-    g_timer.up_only = true;
+int moe_timer_destroy(moe_timer* t) {
+    if (t == nullptr) return MOE_OK;
+    if (t->ev != nullptr) {
+        for (int i = 0; i < t->cap * kStageEvents; ++i)
+            if (t->ev[i]) (void)hipEventDestroy(t->ev[i]);
+        delete[] t->ev;
+    }
+    delete t;
     return MOE_OK;
 }
 
-int moe_up_kernel_timing_every(int32_t every) {
-    if (!g_timer.on || !g_timer.up_only) return fail(MOE_ERR_INVALID_ARG, "moe_up_kernel_timing_enable was not called");
-    if (every < 1) return fail(MOE_ERR_INVALID_ARG, "every must be at least 1");
-    g_timer.every = every;
-    g_timer.seen = 0;
+int moe_timer_reset(moe_timer* t) {
+    REQUIRE(t, "timer");
+    t->n = 0;
     return MOE_OK;
 }
 
-int moe_up_kernel_timing_read(float* ms, int32_t capacity_calls, int32_t* n_calls) {
-    REQUIRE(n_calls, "n_calls");
-    if (!g_timer.up_only) return fail(MOE_ERR_INVALID_ARG, "moe_up_kernel_timing_enable was not called");
-    *n_calls = g_timer.n;
+int moe_timer_read(moe_timer* t, float* ms, int32_t capacity_calls, int32_t* n_calls) {
+    REQUIRE(t, "timer"); REQUIRE(n_calls, "n_calls");
+    *n_calls = t->n;
     if (ms == nullptr) return MOE_OK;
-    const int n = g_timer.n < capacity_calls ? g_timer.n : capacity_calls;
+    const int n = t->n < capacity_calls ? t->n : capacity_calls;
     for (int c = 0; c < n; ++c) {
-        hipEvent_t* ev = g_timer.ev + kStageEvents * c;
-        MOE_HIP_CHECK(hipEventSynchronize(ev[3]));
-        MOE_HIP_CHECK(hipEventElapsedTime(&ms[c], ev[2], ev[3]));
+        hipEvent_t* ev = t->ev + kStageEvents * c;
+        if (t->mode == MOE_TIME_UP_KERNEL) {
+            MOE_HIP_CHECK(hipEventSynchronize(ev[3]));
+            MOE_HIP_CHECK(hipEventElapsedTime(&ms[c], ev[2], ev[3]));
+        } else {
+            MOE_HIP_CHECK(hipEventSynchronize(ev[kStageEvents - 1]));
+            for (int st = 0; st + 1 < kStageEvents; ++st)
+                MOE_HIP_CHECK(hipEventElapsedTime(&ms[c * (kStageEvents - 1) + st], ev[st], ev[st + 1]));
+        }
     }
-    return MOE_OK;
-}
-
-int moe_stage_timing_read(float* ms, int32_t capacity_calls, int32_t* n_calls) {
-    REQUIRE(n_calls, "n_calls");
-    if (g_timer.up_only) return fail(MOE_ERR_INVALID_ARG, "only the up-projection kernel is being timed");
-    *n_calls = g_timer.n;
-    if (ms == nullptr) return MOE_OK;
-    const int n = g_timer.n < capacity_calls ? g_timer.n : capacity_calls;
-    for (int c = 0; c < n; ++c) {
-        hipEvent_t* ev = g_timer.ev + kStageEvents * c;
-        MOE_HIP_CHECK(hipEventSynchronize(ev[kStageEvents - 1]));
-        for (int st = 0; st + 1 < kStageEvents; ++st)
-            MOE_HIP_CHECK(hipEventElapsedTime(&ms[c * (kStageEvents - 1) + st], ev[st], ev[st + 1]));
-    }
-    return MOE_OK;
-}
-
-int moe_stage_timing_disable(void) {
-    if (g_timer.ev != nullptr) {
-        for (int i = 0; i < g_timer.cap * kStageEvents; ++i)
-            if (g_timer.ev[i]) (void)hipEventDestroy(g_timer.ev[i]);
-        delete[] g_timer.ev;
-    }
-    g_timer = StageTimer();
     return MOE_OK;
 }
 

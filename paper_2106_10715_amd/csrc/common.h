@@ -68,8 +68,11 @@ WsLayout ws_layout(const moe_cfg& c);
 size_t route_scratch_bytes(const moe_cfg& c);
 // Columns of the gate matrix: E for the projection gate, log2(E) sign bits for the hashing gate.
 int gate_columns(const moe_cfg& c);
+// Wg: the gate matrix, or (c.gate_packed) the block launch_pack_gate wrote, gate_packed_bytes(c) bytes.
 int launch_route(const moe_cfg& c, const void* x, const void* Wg, const float* bias, int32_t* idx, float* w,
                  void* scratch, hipStream_t s);
+size_t gate_packed_bytes(const moe_cfg& c);
+int launch_pack_gate(const moe_cfg& c, const void* Wg, void* packed, hipStream_t s);
 int launch_permute(const moe_cfg& c, const void* x, const int32_t* idx, int32_t* counts, int32_t* offsets,
                    int32_t* perm, int32_t* inv, void* Xp, int32_t* chunk_hist, hipStream_t s, int32_t* plan = nullptr,
                    int plan_max_tiles = 0, bool* planned = nullptr);

@@ -888,11 +888,10 @@ int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, 
             y_chunks = (col_groups + ny - 1) / ny;
             return tile_groups * y_chunks * 32 * 8;
         };
-        static const int n_cu = [] {
-            int dev = 0, n = 0;
-            if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-            return n;
-        }();
+        int dev = 0;
+        const DeviceInfo* info = nullptr;
+        if (int rc = device_info(&dev, &info)) return rc;
+        const int n_cu = info->compute_units;
         auto grid_for = [&](long items) { return dim3(static_cast<unsigned>(items < n_cu ? items : n_cu)); };
         if (!plan_ready) {          // else the kernel that batched the tokens has written the work list as well
             hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, s, offsets, e_first, e_count, kTileM, plan,

@@ -235,6 +235,7 @@ int launch_permute(const moe_cfg& c, const void* x, const int32_t* idx, int32_t*
         MOE_LAUNCH_CHECK("permute_small_kernel");
         if (with_plan) *planned = true;
     } else {
+        if (chunk_hist == nullptr) return fail(MOE_ERR_WORKSPACE, "the batching of %d assignments needs scratch memory", A);
         hipLaunchKernelGGL(chunk_hist_kernel, dim3(chunks), dim3(256), 0, s, idx, A, c.E, chunk_hist);
         MOE_LAUNCH_CHECK("chunk_hist_kernel");
         hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), 0, s, chunk_hist, chunks, c.E, counts, offsets);

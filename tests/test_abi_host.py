@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_binding_has_the_same_names():
     for n in ("moe_route", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_layer_forward", "moe_pack_weights",
-              "moe_workspace_bytes", "moe_expert_bytes"):
+              "moe_workspace_bytes", "moe_expert_bytes", "moe_gate_bytes", "moe_pack_gate", "moe_layer_forward_timed"):
         assert callable(getattr(M, n))
 
 
@@ -53,6 +53,7 @@ def test_sizes():
     (dict(T=1, d=64, f=64, E=16, k=9), "k must be"),
     (dict(T=1, d=64, f=64, E=2, renorm=2), "renorm"),
     (dict(T=1, d=64, f=64, E=2, act=3), "act"),
+    (dict(T=1, d=64, f=64, E=2, gate_packed=2), "gate_packed"),
     (dict(T=1 << 20, d=4096, f=10240, E=2), "2^31"),
 ])
 def test_bad_cfg_is_rejected(kw, frag):

@@ -301,32 +301,66 @@ def test_resident_layer_can_be_captured_in_a_graph_and_replayed():
         assert scratch == scratch
 
 
-def test_stage_and_up_kernel_timers_count_the_calls_they_should():
-    """The measurement aids of the library: per-stage events for up to N resident calls, or two events around the
-    up-projection kernel of every `every`-th resident call; neither changes the result."""
+def test_timers_record_the_calls_they_have_room_for_and_change_nothing():
+    """The measurement aid of the library: a timed variant of the resident layer call records events into a
+    timer object of the caller (all five stages, or the up-projection kernel alone); the result is the same
+    bytes, and the plain entry point holds no timing state."""
     wl = W.Workload("timers", T=300, d=256, f=384, E=4, k=1, dtype="bf16", seed=95)
     L = H.build_layer(wl)
     M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)
     torch.cuda.synchronize()
     y_plain = L.y.clone()
-    M.moe_stage_timing_enable(3)
+    stages = M.Timer(3, M.TIME_STAGES)
     for _ in range(5):                                       # only the first three calls have room
-        M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)
+        M.moe_layer_forward_timed(L.cfg, L.x, L.Wg, L.bias, L.packed, L.y, L.ws, stages)
+    M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)      # not timed, not counted
     torch.cuda.synchronize()
-    per_call = M.moe_stage_timing_read(8)
+    per_call = stages.read()
     assert len(per_call) == 3
     assert all(set(c) == set(M.STAGES) and all(v >= 0.0 for v in c.values()) for c in per_call)
     assert all(c["ffn_up"] > 0.0 and c["ffn_down"] > 0.0 for c in per_call)
     assert torch.equal(L.y, y_plain)
-    M.moe_up_kernel_timing_enable(4, 2)                      # replaces the stage timer: calls 0, 2, 4, 6
-    for _ in range(7):
-        M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)
+    ups = M.Timer(4, M.TIME_UP_KERNEL)                       # a second timer, independent of the first
+    for _ in range(3):
+        M.moe_layer_forward_timed(L.cfg, L.x, L.Wg, L.bias, L.packed, L.y, L.ws, ups)
     torch.cuda.synchronize()
-    ups = M.moe_up_kernel_timing_read(8)
-    assert len(ups) == 4 and all(0.0 < u < 50.0 for u in ups)
+    got = ups.read()
+    assert len(got) == 3 and all(0.0 < u < 50.0 for u in got)
+    assert len(stages.read()) == 3
+    ups.reset()
+    assert ups.read() == []
     assert torch.equal(L.y, y_plain)
+    stages.close()
+    ups.close()
     with pytest.raises(M.MoeError):
-        M.moe_stage_timing_read(8)                           # the wrong reader for this timer
-    M.moe_stage_timing_disable()
+        M.Timer(0)                                           # room for at least one call is required
     with pytest.raises(M.MoeError):
-        M.moe_up_kernel_timing_enable(0)                     # room for at least one call is required
+        M.Timer(4, 7)
+
+
+@pytest.mark.parametrize("wl", [
+    W.Workload("gate-once-bf16", T=700, d=512, f=256, E=40, k=2, dtype="bf16", seed=96),
+    W.Workload("gate-once-f32", T=130, d=256, f=128, E=6, k=1, dtype="f32", seed=97),
+    W.Workload("gate-once-hash", T=257, d=256, f=128, E=16, k=1, dtype="bf16", seed=98, gate="hash"),
+], ids=lambda w: w.name)
+def test_gate_packed_once_gives_the_same_bytes(wl):
+    """Section 2.3 freezes the gate: packed once by moe_pack_gate it must give what per-call packing gives."""
+    L = H.build_layer(wl)
+    M.moe_layer_forward(L.cfg, L.x, L.Wg, L.bias, L.packed, None, L.y, L.ws)
+    torch.cuda.synchronize()
+    y_plain = L.y.clone()
+    gate = torch.empty(M.moe_gate_bytes(L.cfg), dtype=torch.uint8, device="cuda")
+    M.moe_pack_gate(L.cfg, L.Wg, gate)
+    cfg1 = L.cfg.with_packed_gate()
+    L.ws.zero_()                                             # nothing the per-call packing left may be used
+    L.y.zero_()
+    M.moe_layer_forward(cfg1, L.x, gate, L.bias, L.packed, None, L.y, L.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(L.y, y_plain)
+    idx0 = torch.empty((wl.T, wl.k), dtype=torch.int32, device="cuda")
+    w0 = torch.empty((wl.T, wl.k), dtype=torch.float32, device="cuda")
+    idx1, w1 = torch.empty_like(idx0), torch.empty_like(w0)
+    M.moe_route(L.cfg, L.x, L.Wg, L.bias, idx0, w0, L.ws)
+    M.moe_route(cfg1, L.x, gate, L.bias, idx1, w1, L.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(idx0, idx1) and torch.equal(w0, w1)
