@@ -130,6 +130,19 @@ int moe_permute(const moe_cfg* cfg, const void* x, const int32_t* idx,
                 void* ws, void* stream);
 
 /*
+ * moe_permute for callers that can neither allocate device memory nor hand over a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation): same arguments without `ws`, same
+ * results bit for bit.  The scratch of the batching kernels (per-chunk expert histograms) lies in a fixed
+ * 256 KiB array inside the library, one copy per device, looked up on the first call on a device; the call
+ * allocates nothing.  Limit: T*k <= 262144 assignments (E <= 256 as everywhere); beyond it MOE_ERR_WORKSPACE
+ * and nothing is launched.  All calls on one device share the array: calls that overlap in time on one device
+ * (different streams or threads) race and must be ordered by the caller; nothing has to be cleared between
+ * calls (every entry that is read is written first by the same call).
+ */
+int moe_permute_static(const moe_cfg* cfg, const void* x, const int32_t* idx,
+                       int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv, void* Xp, void* stream);
+
+/*
  * Expert FFNs on the batched rows: for every expert e with offsets[e] < offsets[e+1] and every row r
  * in that range, Yp[r] = (act(Xp[r] W_gate[e]) * (Xp[r] W_in[e])) W_out[e].  Experts without rows
  * are not read.  The d_ff-wide intermediate is kept in ws in dtype.

@@ -59,6 +59,7 @@ def lib() -> C.CDLL:
             "moe_pack_gate": [cfgp, p, p, p],
             "moe_route": [cfgp, p, p, f32p, i32p, f32p, p, p],
             "moe_permute": [cfgp, p, i32p, i32p, i32p, i32p, i32p, p, p, p],
+            "moe_permute_static": [cfgp, p, i32p, i32p, i32p, i32p, i32p, p, p],
             "moe_expert_ffn": [cfgp, p, i32p, p, p, p, p],
             "moe_combine": [cfgp, p, i32p, f32p, p, p],
             "moe_layer_forward": [cfgp, p, p, f32p, p, p, p, p, p],
@@ -141,6 +142,11 @@ def moe_route(cfg, x, W_g, gate_bias, idx, w, ws, stream=None) -> None:
 def moe_permute(cfg, x, idx, counts, offsets, perm, inv, Xp, ws, stream=None) -> None:
     _check(lib().moe_permute(C.byref(cfg), _ptr(x), _ptr(idx), _ptr(counts), _ptr(offsets), _ptr(perm), _ptr(inv),
                              _ptr(Xp), _ptr(ws), _stream(stream)))
+
+
+def moe_permute_static(cfg, x, idx, counts, offsets, perm, inv, Xp, stream=None) -> None:
+    _check(lib().moe_permute_static(C.byref(cfg), _ptr(x), _ptr(idx), _ptr(counts), _ptr(offsets), _ptr(perm), _ptr(inv),
+                                    _ptr(Xp), _stream(stream)))
 
 
 def moe_expert_ffn(cfg, Xp, offsets, W_packed, Yp, ws, stream=None) -> None:

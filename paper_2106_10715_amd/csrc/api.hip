@@ -202,6 +202,17 @@ int moe_permute(const moe_cfg* cfg, const void* x, const int32_t* idx, int32_t* 
                           static_cast<hipStream_t>(stream));
 }
 
+int moe_permute_static(const moe_cfg* cfg, const void* x, const int32_t* idx, int32_t* counts, int32_t* offsets,
+                       int32_t* perm, int32_t* inv, void* Xp, void* stream) {
+    if (int rc = check_cfg(cfg)) return rc;
+    REQUIRE(counts, "counts"); REQUIRE(offsets, "offsets");
+    if (cfg->T > 0) {
+        REQUIRE(idx, "idx"); REQUIRE(perm, "perm"); REQUIRE(inv, "inv");
+        if (Xp != nullptr) { REQUIRE(x, "x"); REQUIRE_ALIGNED(x, "x"); REQUIRE_ALIGNED(Xp, "Xp"); }
+    }
+    return launch_permute_static(*cfg, x, idx, counts, offsets, perm, inv, Xp, static_cast<hipStream_t>(stream));
+}
+
 int moe_expert_ffn(const moe_cfg* cfg, const void* Xp, const int32_t* offsets, const void* W_packed, void* Yp,
                    void* ws, void* stream) {
     if (int rc = check_cfg(cfg)) return rc;

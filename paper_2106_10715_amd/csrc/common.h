@@ -79,6 +79,11 @@ int launch_permute(const moe_cfg& c, const void* x, const int32_t* idx, int32_t*
 // plan/planned: for short bf16 batches the kernel that batches the tokens also writes the work list of the expert
 // FFN launch over all experts that follows (room for plan_max_tiles row tiles) and sets *planned; the caller then
 // passes plan_ready to launch_expert_ffn.
+// The same with the chunk histograms in a fixed array of the library instead of the caller's workspace (at most
+// permute_static_max_assignments() assignments); never writes a work list.
+int launch_permute_static(const moe_cfg& c, const void* x, const int32_t* idx, int32_t* counts, int32_t* offsets,
+                          int32_t* perm, int32_t* inv, void* Xp, hipStream_t s);
+long permute_static_max_assignments();
 int launch_pack(const moe_cfg& c, const void* Win, const void* Wgate, const void* Wout, void* packed, hipStream_t s);
 // Runs the FFN of experts [e_first, e_first + e_count); W points at the packed block of e_first and
 // consecutive experts are expert_stride_bytes apart.  max_rows bounds the rows those experts can hold

@@ -9,6 +9,17 @@
 #include "common.h"
 #include "ffn_plan.h"
 
+#include <mutex>
+
+// Scratch of moe_permute_static, the variant of moe_permute for callers that can neither allocate nor pass a
+// workspace: the per-chunk expert histograms / running bases of the chunked kernels, [chunks][E] int32, for
+// up to kStaticChunks chunks of kPermChunk assignments and 256 experts.  Every device the library runs on
+// holds its own copy of the array (256 KiB) until the process ends.  In host code the name is only a handle
+// for hipGetSymbolAddress, never an address.
+constexpr int kStaticChunks = 256;
+constexpr int kStaticExperts = 256;
+static __device__ __align__(256) int32_t scratch[kStaticChunks * kStaticExperts];
+
 namespace moe {
 namespace {
 
@@ -252,6 +263,39 @@ int launch_permute(const moe_cfg& c, const void* x, const int32_t* idx, int32_t*
         }
     }
     return MOE_OK;
+}
+
+long permute_static_max_assignments() { return static_cast<long>(kStaticChunks) * kPermChunk; }
+
+int launch_permute_static(const moe_cfg& c, const void* x, const int32_t* idx, int32_t* counts, int32_t* offsets,
+                          int32_t* perm, int32_t* inv, void* Xp, hipStream_t s) {
+    const long A = static_cast<long>(c.T) * c.k;
+    const long chunks = (A + kPermChunk - 1) / kPermChunk;
+    if (chunks > kStaticChunks || c.E > kStaticExperts)
+        return fail(MOE_ERR_WORKSPACE, "moe_permute_static batches at most %ld assignments over at most %d experts "
+                    "(got %ld and %d): its scratch is a fixed array; use moe_permute with a workspace",
+                    permute_static_max_assignments(), kStaticExperts, A, c.E);
+    // the array's address on the current device, looked up once per device
+    constexpr int kMaxDevices = 64;
+    static std::mutex lock;
+    static int32_t* on_device[kMaxDevices] = {};
+    int dev = 0;
+    MOE_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(MOE_ERR_UNSUPPORTED, "device %d: only devices 0..%d are supported", dev, kMaxDevices - 1);
+    int32_t* ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> guard(lock);
+        if (on_device[dev] == nullptr) {
+            void* p = nullptr;
+            MOE_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+            if (p == nullptr) return fail(MOE_ERR_HIP, "hipGetSymbolAddress returned no address for the scratch array");
+            on_device[dev] = static_cast<int32_t*>(p);
+        }
+        ptr = on_device[dev];
+    }
+    // Nothing has to be cleared: the histogram kernel writes all chunks x E entries the two kernels after it
+    // read, whatever an earlier call left in the array.
+    return launch_permute(c, x, idx, counts, offsets, perm, inv, Xp, ptr, s);
 }
 
 }  // namespace moe
