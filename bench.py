@@ -45,7 +45,14 @@ def parse():
                     help="run the workload's layer on this many tokens instead of its own count (a sweep over batch sizes; "
                          "the figure the workload is quoted on is the one without this option)")
     ap.add_argument("--streamed", action="store_true", help="run the workload with host-streamed experts even if it is defined resident")
-    ap.add_argument("--slots", type=int, default=2, help="device slots of the streamed mode")
+    ap.add_argument("--slots", type=int, default=4,
+                    help="device slots of the streamed mode (with 4 or more, the copy stream waits for freed slots once "
+                         "per K/2 copies instead of before every copy)")
+    ap.add_argument("--layers", type=int, default=1,
+                    help="streamed workloads: run a stack of this many layers (own context and slots each, the same host "
+                         "weights, layer l+1 fed with layer l's output) and report what is exposed per layer when the layers "
+                         "run one by one against per model when the next layer's first expert is prefetched under the "
+                         "current layer (Section 6.2: only the first expert waits for its parameters)")
     ap.add_argument("--order", default="ascending", choices=["ascending", "greedy"],
                     help="streamed mode: expert execution order (greedy = the paper's Section 6.2 schedule)")
     ap.add_argument("--keep-experts", action="store_true",
@@ -223,6 +230,76 @@ def streamed_leg(M, torch, np, cfg, x, gate, bias, host_packed, y, ws, wl, steps
     return ms_per_step, roof, rec, counts.cpu().numpy()
 
 
+def stack_leg(M, torch, np, cfg, x, gate, bias, host_packed, wl, n_layers, n_slots, steps, warmup):
+    """A stack of streamed layers (each with its own context and slots; layer l+1 reads layer l's output; all layers load
+    through the copy streams of the first, moe_stream_ctx_share_loader).  Slots keep their experts, so that an expert
+    requested ahead of its layer's call is found resident by it:
+      one by one   every layer's call is waited for before the next is issued, nothing is requested ahead
+      pipelined    as soon as the call of layer l has returned (its loads are queued), the first expert of layer l+1 is
+                   requested (moe_stream_ctx_prefetch), so that it is loaded while layer l finishes and layer l+1
+                   routes; the calls follow each other without a wait in between
+    Both load every non-empty expert of every layer in every pass (what the slots hold is forgotten between passes)."""
+    eb = M.moe_expert_bytes(cfg)
+    ctxs, keep = [], []
+    for _ in range(n_layers):
+        slots = torch.empty((n_slots, eb), dtype=torch.uint8, device="cuda")
+        ctx = M.StreamCtx(cfg, host_packed, slots, n_slots)
+        if ctxs:
+            ctx.share_loader(ctxs[0])            # one loader (two copy streams) for the whole stack
+        ctxs.append(ctx)
+        keep.append(slots)
+    ws = torch.empty(M.moe_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+    acts = [x] + [torch.empty_like(x) for _ in range(n_layers)]
+    counts = torch.empty(cfg.E, dtype=torch.int32, device="cuda")
+
+    def first_expert(l):
+        """The expert layer l will run first (ascending order: its lowest non-empty expert), by the staged calls."""
+        idx = torch.empty((wl.T, wl.k), dtype=torch.int32, device="cuda")
+        w = torch.empty((wl.T, wl.k), dtype=torch.float32, device="cuda")
+        offsets = torch.empty(cfg.E + 1, dtype=torch.int32, device="cuda")
+        perm = torch.empty(wl.A, dtype=torch.int32, device="cuda")
+        inv = torch.empty(wl.A, dtype=torch.int32, device="cuda")
+        M.moe_route(cfg, acts[l], gate, bias, idx, w, ws)
+        M.moe_permute(cfg, acts[l], idx, counts, offsets, perm, inv, None, ws)
+        torch.cuda.synchronize()
+        return int(np.nonzero(counts.cpu().numpy())[0][0])
+
+    def one_pass(pipelined, firsts):
+        for ctx in ctxs:                         # every pass loads everything: forget what the slots hold
+            ctx.keep_experts(False)
+            ctx.keep_experts(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ends = []
+        for l in range(n_layers):
+            M.moe_layer_forward(cfg, acts[l], gate, bias, None, ctxs[l], acts[l + 1], ws)
+            if pipelined and l + 1 < n_layers:
+                ctxs[l + 1].prefetch(firsts[l + 1])
+            if not pipelined:
+                torch.cuda.synchronize()
+                ends.append((time.perf_counter() - t0) * 1e3)
+        torch.cuda.synchronize()
+        per_layer.append([round(b - a, 3) for a, b in zip([0.0] + ends, ends)])
+        return (time.perf_counter() - t0) * 1e3, sum(c.stats()["n_loaded"] for c in ctxs)
+
+    per_layer = []
+    # a first pass fixes the activations of every layer (and with them which expert each layer runs first)
+    one_pass(False, None)
+    firsts = [first_expert(l) for l in range(n_layers)]
+    res = {}
+    for name, pipelined in (("one_by_one", False), ("pipelined", True)):
+        for _ in range(warmup):
+            one_pass(pipelined, firsts)
+        ms, loads = zip(*[one_pass(pipelined, firsts) for _ in range(steps)])
+        res[name] = {"ms_per_pass": float(np.mean(ms)), "ms_passes": [round(float(v), 3) for v in ms],
+                     "loads_in_calls_per_pass": float(np.mean(loads))}
+        if not pipelined:
+            res[name]["ms_per_layer_last_pass"] = per_layer[-1]
+    for c in reversed(ctxs):                     # the owner of the shared copy stream last
+        c.close()
+    return res
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -283,6 +360,18 @@ def main():
                                                       args.tokens_per_load)
         out["roofline"] = roof
         out["streaming"] = rec
+        if args.layers > 1:
+            st = stack_leg(M, torch, np, cfg, L.x, gate, L.bias, L.host_packed, wl, args.layers, args.slots,
+                           max(3, args.steps // 4), 2)
+            if "copy_alone_ms" in rec:
+                for v in st.values():
+                    if not isinstance(v, dict):
+                        continue
+                    v["exposed_ms_per_pass"] = v["ms_per_pass"] - args.layers * rec["copy_alone_ms"]
+                    v["exposed_ms_per_layer"] = v["exposed_ms_per_pass"] / args.layers
+            out["stack"] = {"layers": args.layers, **st,
+                            "note": "exposed = pass time - layers x (the same copies alone); one_by_one pays the first load's "
+                                    "lead-in and the last expert's tail once per layer, pipelined once per model"}
     else:
         def step():
             M.moe_layer_forward(cfg, L.x, gate, L.bias, L.packed, None, L.y, L.ws)

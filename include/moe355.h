@@ -19,7 +19,7 @@
  *     idx/counts/offsets/perm/inv are int32; gate weights w and the gate bias are fp32.
  *   - The caller owns every buffer.  The library never allocates or frees device memory; scratch
  *     is the caller's workspace `ws` of at least moe_workspace_bytes() bytes, 256-byte aligned.
- *     (Only moe_stream_ctx_create allocates: one copy stream, a few events and a small pinned
+ *     (Only moe_stream_ctx_create allocates: two copy streams, a few events and a small pinned
  *     host buffer, all released by moe_stream_ctx_destroy.)
  *   - Calls are asynchronous: work is enqueued on `stream` (a hipStream_t passed as void*, NULL =
  *     the default stream) and the call returns.  The one exception is moe_layer_forward in
@@ -172,11 +172,13 @@ int moe_combine(const moe_cfg* cfg, const void* Yp, const int32_t* inv, const fl
  *   After route + permute the call copies counts[E] to the host and waits for it (the host must know
  *   which experts have tokens; Section 6.2 sizes an expert's compute by its token count), then runs the
  *   non-empty experts in the order of the context (ascending id unless moe_stream_ctx_set_order chose the
- *   greedy order of Section 6.2): each expert's packed block is copied into one of the K device slots on the
- *   context's copy stream while earlier experts compute on `stream`; events order copy-before-compute and
+ *   greedy order of Section 6.2): each expert's packed block is copied into one of the K device slots on one of the
+ *   context's two copy streams (taking turns) while earlier experts compute on `stream`; events order copy-before-compute and
  *   compute-before-slot-reuse.  Experts without tokens are not loaded.  Every call loads every non-empty
  *   expert, unless moe_stream_ctx_keep_experts lets the slots keep theirs between calls (then only experts
- *   no slot holds are loaded).  The call returns with the remaining work enqueued on `stream`.  If the
+ *   no slot holds are loaded).  From the second call on a context in ascending order, the load of the expert the
+ *   previous call ran first is requested before the gate runs (it is very likely the first again; a wrong guess
+ *   costs one wasted copy).  The call returns with the remaining work enqueued on `stream`.  If the
  *   call fails half-way, the context forgets what its slots hold (nothing is taken for resident that may
  *   not have been copied).
  *   Results are bitwise identical in both modes.
@@ -262,8 +264,16 @@ int moe_stream_ctx_last_order(const moe_stream_ctx* sctx, int32_t* order, int32_
  * moe_plan_slots is the replacement rule itself as a pure host function (all arrays host memory):
  *   order [n] experts in execution order;  slot_expert [K] in/out, -1 = empty;  slot_tick [K] in/out, when
  *   each slot was last used;  *tick in/out use counter;  slot_of [n], load [n] (1 = must be loaded) out.
+ *
+ * moe_stream_ctx_share_loader(sctx, owner): from now on sctx enqueues its loads on owner's copy streams instead of its
+ * own, so that the loads of both contexts run one after the other in the order they were requested (one loader for
+ * the whole model, as in Section 6.2's timeline) instead of side by side.  With the layers of a model sharing one
+ * loader, a prefetch for layer l+1 issued right after the call of layer l has returned is queued behind layer l's last
+ * load and runs while layer l finishes computing and layer l+1 routes.  Waits until sctx's own loads have finished.
+ * owner must be a context with copy streams of its own, on the same device, and must be destroyed after sctx.
  */
 int moe_stream_slots_that_fit(const moe_cfg* cfg, size_t reserve_bytes, int32_t* K);
+int moe_stream_ctx_share_loader(moe_stream_ctx* sctx, moe_stream_ctx* owner);
 int moe_stream_ctx_keep_experts(moe_stream_ctx* sctx, int32_t on);
 int moe_stream_ctx_prefetch(moe_stream_ctx* sctx, int32_t expert);
 int moe_plan_slots(const int32_t* order, int32_t n, int32_t K, int32_t* slot_expert, int64_t* slot_tick, int64_t* tick,
@@ -272,7 +282,7 @@ int moe_plan_slots(const int32_t* order, int32_t n, int32_t K, int32_t* slot_exp
 /*
  * Figures of the last streamed moe_layer_forward on this context; waits for that call's work to
  * finish.  n_loaded = experts copied; bytes = n_loaded * expert_bytes; copy_ms = first copy start to
- * last copy end on the copy stream.  Any pointer may be NULL.
+ * last copy end on the copy streams.  Any pointer may be NULL.
  */
 int moe_stream_ctx_stats(moe_stream_ctx* sctx, int32_t* n_loaded, size_t* bytes, float* copy_ms);
 

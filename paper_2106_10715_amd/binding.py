@@ -73,6 +73,7 @@ def lib() -> C.CDLL:
             "moe_stream_slots_that_fit": [C.POINTER(MoeCfg), C.c_size_t, C.POINTER(C.c_int32)],
             "moe_stream_ctx_keep_experts": [p, C.c_int32],
             "moe_stream_ctx_prefetch": [p, C.c_int32],
+            "moe_stream_ctx_share_loader": [p, p],
             "moe_plan_slots": [C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int64),
                                C.POINTER(C.c_int64), C.POINTER(C.c_int32), C.POINTER(C.c_int32)],
             "moe_timer_create": [C.c_int32, C.c_int32, C.POINTER(C.c_void_p)],
@@ -183,6 +184,10 @@ class StreamCtx:
 
     def keep_experts(self, on: bool = True) -> None:
         _check(lib().moe_stream_ctx_keep_experts(self._h, 1 if on else 0))
+
+    def share_loader(self, owner: "StreamCtx") -> None:
+        _check(lib().moe_stream_ctx_share_loader(self._h, owner.handle))
+        self._owner = owner                      # the owner's stream must outlive this context
 
     def prefetch(self, expert: int) -> None:
         _check(lib().moe_stream_ctx_prefetch(self._h, int(expert)))

@@ -99,16 +99,35 @@ struct moe_stream_ctx {
     char* dev_slots;
     int K;
     int device;
-    hipStream_t copy_stream;
+    // Loads alternate between two copy streams: after every copy the stream has an event to process (the compute
+    // stream waits for it) before its next copy may start, some 30 us during which the link would idle; with two
+    // streams the other one's copy is running meanwhile (measured on 32 copies of 240 MiB: 141.97 ms with one
+    // stream, 141.13 ms with two, 140.82 ms for the bare copies).
+    // The streams are created when the first load needs them: a context that shares another one's loader never
+    // creates any (HIP maps all streams of a process onto a few hardware queues, 4 by default, and a copy stream
+    // that lands on the hardware queue of the compute stream waits behind its kernels).
+    hipStream_t copy_streams[2];
+    bool owns_copy_streams;           // false: the streams belong to another context (moe_stream_ctx_share_loader)
+    moe_stream_ctx* loader;           // the context whose streams are used, if not this one's own
+    int next_copy;                    // which of the two takes the next load
+    int slot_writer[kMaxSlots];       // copy stream of the last load into each slot; -1 once a compute has read it
     hipEvent_t loaded[kMaxSlots];     // copy into slot s finished
     hipEvent_t released[kMaxSlots];   // compute that read slot s finished
     bool released_valid[kMaxSlots];
+    // Slot reuse: every release is recorded on the compute stream and numbered; a copy stream that has waited for
+    // release number n has waited for all releases up to n recorded on that same stream (a stream runs in order),
+    // so a copy into a slot needs a wait only if the slot's last release is newer than that.
+    int64_t release_seq[kMaxSlots];   // number of the last release recorded for each slot (0: never used)
+    int64_t seq;                      // releases recorded so far
+    int64_t copy_waited_seq[2];       // each copy stream has waited for the release with this number
+    hipStream_t release_stream;       // the compute stream those numbers belong to
     bool keep;                        // slots keep their experts between calls
     int32_t slot_expert[kMaxSlots];   // expert held by each slot, -1 = none (only meaningful with keep)
     int64_t slot_tick[kMaxSlots];     // when each slot was last used
     int64_t tick;
     int n_order;                      // experts run by the last call
-    hipEvent_t first_copy, last_copy;
+    hipEvent_t first_copy, last_copy[2];
+    int timed_streams;                // bit q: last_copy[q] was recorded by the last call
     bool timed;
     int32_t* h_counts;         // pinned [256]
     int n_loaded;
@@ -251,6 +270,44 @@ struct SlotGuard {
     }
 };
 
+// Records that the compute on `s` which read `slot` is done (everything enqueued on `s` so far).
+int record_release(moe_stream_ctx* ctx, int slot, hipStream_t s) {
+    MOE_HIP_CHECK(hipEventRecord(ctx->released[slot], s));
+    ctx->released_valid[slot] = true;
+    ctx->release_seq[slot] = ++ctx->seq;
+    ctx->slot_writer[slot] = -1;
+    return MOE_OK;
+}
+
+// Enqueues the copy of expert e into `slot` on the copy stream whose turn it is.  The copy must follow the slot's
+// last reader (a wait for its release, unless that stream has already waited for this or a later release of the
+// compute stream) and, if the slot was loaded on the other copy stream and never read since (a load requested
+// ahead that turned out not to be needed), that load.
+int enqueue_load(moe_stream_ctx* ctx, int e, int slot) {
+    const int q = ctx->next_copy;
+    ctx->next_copy ^= 1;
+    if (ctx->copy_streams[q] == nullptr) {
+        moe_stream_ctx* owner = ctx->loader != nullptr ? ctx->loader : ctx;
+        if (owner->copy_streams[q] == nullptr)
+            MOE_HIP_CHECK(hipStreamCreateWithFlags(&owner->copy_streams[q], hipStreamNonBlocking));
+        ctx->copy_streams[q] = owner->copy_streams[q];
+    }
+    hipStream_t cs = ctx->copy_streams[q];
+    if (ctx->released_valid[slot] && ctx->release_seq[slot] > ctx->copy_waited_seq[q]) {
+        MOE_HIP_CHECK(hipStreamWaitEvent(cs, ctx->released[slot], 0));
+        ctx->copy_waited_seq[q] = ctx->release_seq[slot];
+    }
+    if (ctx->slot_writer[slot] >= 0 && ctx->slot_writer[slot] != q) MOE_HIP_CHECK(hipStreamWaitEvent(cs, ctx->loaded[slot], 0));
+    if (ctx->n_loaded == 0) MOE_HIP_CHECK(hipEventRecord(ctx->first_copy, cs));
+    MOE_HIP_CHECK(hipMemcpyAsync(ctx->dev_slots + static_cast<size_t>(slot) * ctx->expert_bytes,
+                                 ctx->host_experts + static_cast<size_t>(e) * ctx->expert_bytes, ctx->expert_bytes,
+                                 hipMemcpyHostToDevice, cs));
+    MOE_HIP_CHECK(hipEventRecord(ctx->loaded[slot], cs));
+    ctx->slot_writer[slot] = q;
+    ++ctx->n_loaded;
+    return MOE_OK;
+}
+
 // The layer; `timer` (resident mode only) receives this call's events if it has room.
 int layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const float* gate_bias, const void* W_packed,
                   moe_stream_ctx* sctx, void* y, void* ws, void* stream, moe_timer* timer) {
@@ -289,6 +346,31 @@ int layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const floa
     const bool direct = c.dtype == MOE_BF16 && c.k == 1 && (c.renorm == 1 || c.gate == MOE_GATE_HASH);
     void* ffn_out = direct ? y : static_cast<void*>(base + L.Yp);
     const int32_t* row_map = direct ? perm : nullptr;
+
+    int early = -1;                // streamed mode: the expert requested before routing, if any
+    if (sctx != nullptr) {
+        // the release numbers are only ordered among releases of one compute stream: on another stream, wait for
+        // every slot's last reader once and start over
+        if (sctx->release_stream != s) {
+            for (int q = 0; q < 2; ++q) {
+                for (int i = 0; i < sctx->K && sctx->copy_streams[q] != nullptr; ++i)
+                    if (sctx->released_valid[i]) MOE_HIP_CHECK(hipStreamWaitEvent(sctx->copy_streams[q], sctx->released[i], 0));
+                // (a stream that does not exist yet has no copies on it; what it has "waited for" only matters
+                // for releases recorded from now on, which carry higher numbers)
+                sctx->copy_waited_seq[q] = sctx->copy_streams[q] != nullptr ? sctx->seq : 0;
+            }
+            sctx->release_stream = s;
+        }
+        sctx->n_loaded = 0;
+        // Every expert but the first is loaded while earlier ones compute (Section 6.2); the first load has
+        // nothing of its own call to hide behind except the routing.  When every call reloads every expert in
+        // ascending order, the first expert of the previous call is very likely the first of this one: its load is
+        // requested now, before the gate runs.  (A wrong guess costs one wasted copy; the slot is loaded again.)
+        if (!sctx->keep && sctx->policy == MOE_ORDER_ASCENDING && sctx->n_order > 0) {
+            early = sctx->order[0];
+            if (int rc = enqueue_load(sctx, early, 0)) return rc;
+        }
+    }
 
     hipEvent_t* tev = nullptr;     // this call's events, if it is timed and the timer has room
     if (timer != nullptr && timer->n < timer->cap) tev = timer->ev + kStageEvents * timer->n++;
@@ -353,10 +435,8 @@ int layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const floa
             if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, 0, c.E, sctx->dev_slots, eb, A, base + L.H, ffn_out,
                                            reinterpret_cast<int32_t*>(base + L.ffn_plan), s, nullptr, nullptr, row_map))
                 return rc;
-            for (int pos = 0; pos < n_order; ++pos) {
-                MOE_HIP_CHECK(hipEventRecord(sctx->released[slot_of[pos]], s));
-                sctx->released_valid[slot_of[pos]] = true;
-            }
+            for (int pos = 0; pos < n_order; ++pos)
+                if (int rc = record_release(sctx, slot_of[pos], s)) return rc;
             sctx->n_order = n_order;
             sctx->n_loaded = 0;
             sctx->timed = false;
@@ -365,32 +445,26 @@ int layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const floa
             sctx->n_order = n_order;
         }
         const bool grouped = n_order == 0 && sctx->n_order > 0 && all_fit;
-        int i = 0;
         for (int pos = 0; pos < n_order; ++pos) {
             const int e = sctx->order[pos];
             const int n_e = sctx->h_counts[e];
             const int slot = slot_of[pos];
             char* dst = sctx->dev_slots + static_cast<size_t>(slot) * eb;
-            if (load[pos]) {
-                // the load may not overwrite a slot an earlier expert (of this or a previous call) still reads
-                if (sctx->released_valid[slot]) MOE_HIP_CHECK(hipStreamWaitEvent(sctx->copy_stream, sctx->released[slot], 0));
-                if (i == 0) MOE_HIP_CHECK(hipEventRecord(sctx->first_copy, sctx->copy_stream));
-                MOE_HIP_CHECK(hipMemcpyAsync(dst, sctx->host_experts + static_cast<size_t>(e) * eb, eb, hipMemcpyHostToDevice,
-                                             sctx->copy_stream));
-                MOE_HIP_CHECK(hipEventRecord(sctx->loaded[slot], sctx->copy_stream));
-                ++i;
+            if (load[pos] && !(pos == 0 && early == e)) {       // (the first expert may have been requested before routing)
+                if (int rc = enqueue_load(sctx, e, slot)) return rc;
             }
             MOE_HIP_CHECK(hipStreamWaitEvent(s, sctx->loaded[slot], 0));   // also when kept: its load may still be running
             if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, e, 1, dst, eb, n_e, base + L.H, ffn_out,
                                            reinterpret_cast<int32_t*>(base + L.ffn_plan), s, nullptr, nullptr, row_map))
                 return rc;
-            MOE_HIP_CHECK(hipEventRecord(sctx->released[slot], s));
-            sctx->released_valid[slot] = true;
+            if (int rc = record_release(sctx, slot, s)) return rc;
         }
         if (!grouped) {
-            if (i > 0) MOE_HIP_CHECK(hipEventRecord(sctx->last_copy, sctx->copy_stream));
-            sctx->n_loaded = i;
-            sctx->timed = i > 0;
+            if (sctx->n_loaded > 0)
+                for (int q = 0; q < 2; ++q)
+                    if (sctx->copy_streams[q] != nullptr) MOE_HIP_CHECK(hipEventRecord(sctx->last_copy[q], sctx->copy_streams[q]));
+            sctx->timed_streams = (sctx->copy_streams[0] != nullptr ? 1 : 0) | (sctx->copy_streams[1] != nullptr ? 2 : 0);
+            sctx->timed = sctx->n_loaded > 0;
         }
         guard.ok = true;
     }
@@ -495,13 +569,14 @@ int moe_stream_ctx_create(const moe_cfg* cfg, const void* host_experts, size_t e
     ctx->K = K;
     for (int i = 0; i < kMaxSlots; ++i) ctx->slot_expert[i] = -1;
     hipError_t e = hipGetDevice(&ctx->device);
-    if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->copy_stream, hipStreamNonBlocking);
+    for (int i = 0; i < kMaxSlots; ++i) ctx->slot_writer[i] = -1;
+    ctx->owns_copy_streams = true;
     for (int i = 0; i < K && e == hipSuccess; ++i) {
         e = hipEventCreateWithFlags(&ctx->loaded[i], hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->released[i], hipEventDisableTiming);
     }
     if (e == hipSuccess) e = hipEventCreate(&ctx->first_copy);
-    if (e == hipSuccess) e = hipEventCreate(&ctx->last_copy);
+    for (int q = 0; q < 2 && e == hipSuccess; ++q) e = hipEventCreate(&ctx->last_copy[q]);
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&ctx->h_counts), 256 * sizeof(int32_t), hipHostMallocDefault);
     if (e != hipSuccess) {
         const int rc = fail(MOE_ERR_HIP, "creating the stream context failed: %s", hipGetErrorString(e));
@@ -573,11 +648,29 @@ int moe_stream_ctx_prefetch(moe_stream_ctx* ctx, int32_t expert) {
         return rc;
     }
     if (!load) return MOE_OK;
-    if (ctx->released_valid[slot]) MOE_HIP_CHECK(hipStreamWaitEvent(ctx->copy_stream, ctx->released[slot], 0));
-    MOE_HIP_CHECK(hipMemcpyAsync(ctx->dev_slots + static_cast<size_t>(slot) * ctx->expert_bytes,
-                                 ctx->host_experts + static_cast<size_t>(expert) * ctx->expert_bytes, ctx->expert_bytes,
-                                 hipMemcpyHostToDevice, ctx->copy_stream));
-    MOE_HIP_CHECK(hipEventRecord(ctx->loaded[slot], ctx->copy_stream));
+    const int before = ctx->n_loaded;             // a load requested ahead is not one of a call's own loads
+    const int rc = enqueue_load(ctx, expert, slot);
+    ctx->n_loaded = before;
+    if (rc != MOE_OK) ctx->slot_expert[slot] = -1;   // not taken for resident unless its copy is on its way
+    return rc;
+}
+
+int moe_stream_ctx_share_loader(moe_stream_ctx* ctx, moe_stream_ctx* owner) {
+    REQUIRE(ctx, "sctx"); REQUIRE(owner, "owner");
+    if (ctx == owner) return MOE_OK;
+    if (!owner->owns_copy_streams) return fail(MOE_ERR_INVALID_ARG, "the owner must be a context that loads on its own streams");
+    if (ctx->device != owner->device) return fail(MOE_ERR_INVALID_ARG, "both contexts must live on the same device");
+    if (ctx->loader == owner) return MOE_OK;
+    for (int q = 0; q < 2; ++q) {
+        if (ctx->copy_streams[q] != nullptr) {
+            MOE_HIP_CHECK(hipStreamSynchronize(ctx->copy_streams[q]));      // nothing of this context is left on its old streams
+            if (ctx->owns_copy_streams) MOE_HIP_CHECK(hipStreamDestroy(ctx->copy_streams[q]));
+        }
+        ctx->copy_streams[q] = nullptr;                                     // taken from the owner at the next load
+        ctx->copy_waited_seq[q] = 0;                                        // nothing has been waited for on the new streams
+    }
+    ctx->owns_copy_streams = false;
+    ctx->loader = owner;
     return MOE_OK;
 }
 
@@ -605,13 +698,18 @@ int moe_stream_ctx_last_order(const moe_stream_ctx* ctx, int32_t* order, int32_t
 
 int moe_stream_ctx_destroy(moe_stream_ctx* ctx) {
     if (ctx == nullptr) return MOE_OK;
-    if (ctx->copy_stream) { (void)hipStreamSynchronize(ctx->copy_stream); (void)hipStreamDestroy(ctx->copy_stream); }
+    for (int q = 0; q < 2; ++q) {
+        if (ctx->copy_streams[q] == nullptr) continue;
+        (void)hipStreamSynchronize(ctx->copy_streams[q]);
+        if (ctx->owns_copy_streams) (void)hipStreamDestroy(ctx->copy_streams[q]);
+    }
     for (int i = 0; i < kMaxSlots; ++i) {
         if (ctx->loaded[i]) (void)hipEventDestroy(ctx->loaded[i]);
         if (ctx->released[i]) (void)hipEventDestroy(ctx->released[i]);
     }
     if (ctx->first_copy) (void)hipEventDestroy(ctx->first_copy);
-    if (ctx->last_copy) (void)hipEventDestroy(ctx->last_copy);
+    for (int q = 0; q < 2; ++q)
+        if (ctx->last_copy[q]) (void)hipEventDestroy(ctx->last_copy[q]);
     if (ctx->h_counts) (void)hipHostFree(ctx->h_counts);
     delete ctx;
     return MOE_OK;
@@ -621,8 +719,13 @@ int moe_stream_ctx_stats(moe_stream_ctx* ctx, int32_t* n_loaded, size_t* bytes, 
     REQUIRE(ctx, "sctx");
     float ms = 0.f;
     if (ctx->timed) {
-        MOE_HIP_CHECK(hipEventSynchronize(ctx->last_copy));
-        MOE_HIP_CHECK(hipEventElapsedTime(&ms, ctx->first_copy, ctx->last_copy));
+        for (int q = 0; q < 2; ++q) {             // the later end of the two copy streams
+            if (!((ctx->timed_streams >> q) & 1)) continue;
+            float to_end = 0.f;
+            MOE_HIP_CHECK(hipEventSynchronize(ctx->last_copy[q]));
+            MOE_HIP_CHECK(hipEventElapsedTime(&to_end, ctx->first_copy, ctx->last_copy[q]));
+            ms = to_end > ms ? to_end : ms;
+        }
     }
     if (n_loaded) *n_loaded = ctx->n_loaded;
     if (bytes) *bytes = static_cast<size_t>(ctx->n_loaded) * ctx->expert_bytes;

@@ -271,6 +271,106 @@ def test_prefetched_expert_is_resident_when_the_layer_runs():
     ctx.close()
 
 
+def test_slots_that_fit_is_bounded_by_free_memory_when_that_is_the_smaller_bound():
+    """Section 6.2: K set by the caller or derived from the memory there is.  With most of the free memory
+    reserved, the memory and not the expert count decides."""
+    cfg = M.MoeCfg.make(512, 4096, 10240, 32)                    # 240 MiB per expert
+    eb = M.moe_expert_bytes(cfg)
+    free, _ = torch.cuda.mem_get_info()
+    assert M.moe_stream_slots_that_fit(cfg, reserve_bytes=0) == 32 or free < 32 * eb
+    for want in (1, 2, 5):
+        K = M.moe_stream_slots_that_fit(cfg, reserve_bytes=free - want * eb - eb // 2)
+        assert K in (want - 1, want), f"{K} slots for room for {want}.5 experts"      # other users of the device may take a little
+    assert M.moe_stream_slots_that_fit(cfg, reserve_bytes=free + (1 << 30)) == 0
+
+
+@pytest.mark.parametrize("K", [2, 4, 7])
+def test_stack_of_streamed_layers_with_the_next_layers_first_expert_requested_ahead(K):
+    """Section 6.2: only the first expert waits for its parameters.  In a stack of layers that holds once per
+    model if the first expert of layer l+1 is loaded while layer l finishes: three layers with their own weights,
+    contexts and slots, each fed with the previous layer's output, all loading through one copy stream, the first
+    expert of the next layer requested as soon as a layer's call has returned; the streamed stack must equal the
+    resident stack bit for bit, and every layer's call must find its first expert resident."""
+    n_layers = 3
+    wls = [W.Workload(f"stack{l}", T=350, d=256, f=384, E=6, k=1, dtype="bf16", seed=300 + l) for l in range(n_layers)]
+    layers = [H.build_layer(wl, host_copy=True) for wl in wls]
+    cfg = layers[0].cfg
+    acts = [layers[0].x] + [torch.empty_like(layers[0].x) for _ in range(n_layers)]
+    ws = layers[0].ws
+    live = []
+    for l, Ly in enumerate(layers):                              # resident stack; also which experts every layer uses
+        M.moe_layer_forward(cfg, acts[l], Ly.Wg, None, Ly.packed, None, acts[l + 1], ws)
+        idx = torch.empty((350, 1), dtype=torch.int32, device="cuda")
+        w = torch.empty((350, 1), dtype=torch.float32, device="cuda")
+        M.moe_route(cfg, acts[l], Ly.Wg, None, idx, w, ws)
+        torch.cuda.synchronize()
+        live.append(sorted(set(idx.flatten().tolist())))
+    want = [a.clone() for a in acts[1:]]
+    eb = M.moe_expert_bytes(cfg)
+    ctxs, slots = [], []
+    for Ly in layers:
+        slots.append(torch.empty((K, eb), dtype=torch.uint8, device="cuda"))
+        ctxs.append(M.StreamCtx(cfg, Ly.host_packed, slots[-1], K))
+        ctxs[-1].keep_experts(True)
+    for ctx in ctxs[1:]:
+        ctx.share_loader(ctxs[0])                                # one loader for the whole stack
+    with pytest.raises(M.MoeError):
+        ctxs[0].share_loader(ctxs[1])                            # only a context with its own stream can be shared
+    for rep in range(2):
+        for ctx in ctxs:                                         # every pass starts with empty slots
+            ctx.keep_experts(False)
+            ctx.keep_experts(True)
+        for a in acts[1:]:
+            a.fill_(float("nan"))
+        ctxs[0].prefetch(live[0][0])
+        for l, Ly in enumerate(layers):                          # no wait between the layers
+            M.moe_layer_forward(cfg, acts[l], Ly.Wg, None, None, ctxs[l], acts[l + 1], ws)
+            if l + 1 < n_layers:
+                ctxs[l + 1].prefetch(live[l + 1][0])             # queued behind layer l's last load
+        torch.cuda.synchronize()
+        for l in range(n_layers):
+            assert torch.equal(acts[l + 1], want[l]), f"layer {l}, pass {rep}"
+            assert ctxs[l].stats()["n_loaded"] == len(live[l]) - 1, f"layer {l}: its first expert was requested ahead"
+    for ctx in reversed(ctxs):                                   # the owner of the shared stream last
+        ctx.close()
+
+
+@pytest.mark.parametrize("K", [4, 5, 8])
+def test_streamed_calls_in_a_row_with_many_slots_and_the_first_load_requested_before_routing(K):
+    """With four or more slots the copy stream waits for freed slots once per K/2 copies, and from the second call
+    on the first expert's load is requested before the gate runs.  Neither may change a byte, whether the guess of the
+    first expert is right (same tokens again) or wrong (other tokens, whose first expert differs), and also when the
+    calls move to another stream."""
+    wl = W.Workload("many-slots", T=500, d=256, f=384, E=24, k=2, dtype="bf16", seed=310, zipf_s=0.8, n_dead=2)
+    L = H.build_layer(wl, host_copy=True)
+    cfg, eb = L.cfg, M.moe_expert_bytes(L.cfg)
+    idx = torch.empty((wl.T, wl.k), dtype=torch.int32, device="cuda")
+    w = torch.empty((wl.T, wl.k), dtype=torch.float32, device="cuda")
+    M.moe_route(cfg, L.x, L.Wg, L.bias, idx, w, L.ws)
+    torch.cuda.synchronize()
+    first = int(idx.min())                                       # the expert the first batch runs first
+    bias2 = L.bias.clone()
+    bias2[first] = -1.0e9                                        # the other batch never uses it: the guess will be wrong
+    outs = {}
+    for name, b in (("a", L.bias), ("b", bias2)):
+        M.moe_layer_forward(cfg, L.x, L.Wg, b, L.packed, None, L.y, L.ws)
+        torch.cuda.synchronize()
+        outs[name] = L.y.clone()
+    assert not torch.equal(outs["a"], outs["b"])
+    slots = torch.empty((K, eb), dtype=torch.uint8, device="cuda")
+    ctx = M.StreamCtx(cfg, L.host_packed, slots, K)
+    side = torch.cuda.Stream()
+    for i, name in enumerate("aabbaba"):
+        L.y.fill_(float("nan"))
+        stream = side if i in (3, 4) else None
+        if stream is not None:
+            side.wait_stream(torch.cuda.current_stream())
+        M.moe_layer_forward(cfg, L.x, L.Wg, L.bias if name == "a" else bias2, None, ctx, L.y, L.ws, stream=stream)
+        torch.cuda.synchronize()
+        assert torch.equal(L.y, outs[name]), f"call {i} ({name}), K={K}"
+    ctx.close()
+
+
 def test_resident_layer_can_be_captured_in_a_graph_and_replayed():
     """The resident layer is kernels only (its counters are cleared by a kernel, not by a memset), so it can
     be recorded once and replayed; every replay, with other work in between, must equal the eager result."""
