@@ -36,7 +36,8 @@ class MoeCfg(C.Structure):
 
 
 def lib_path() -> str:
-    return os.path.join(_HERE, "libmoe355.so")
+    """The library next to this file, or the build named by the environment variable MOE355_LIB."""
+    return os.environ.get("MOE355_LIB") or os.path.join(_HERE, "libmoe355.so")
 
 
 def lib() -> C.CDLL:

@@ -346,6 +346,13 @@ int layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const floa
     const bool direct = c.dtype == MOE_BF16 && c.k == 1 && (c.renorm == 1 || c.gate == MOE_GATE_HASH);
     void* ffn_out = direct ? y : static_cast<void*>(base + L.Yp);
     const int32_t* row_map = direct ? perm : nullptr;
+    // With few rows per expert (the layer is then bound by streaming the weights, and every microsecond beside the
+    // expert kernels counts) the up-projection reads its rows from x through the permutation itself: the batched
+    // copy Xp is neither written nor read.  Row tiles are then slightly lower, which costs experts with many rows
+    // an extra pass over their weights, hence the bound on the mean.
+    const bool gather_rows = c.dtype == MOE_BF16 && A / c.E <= 160;
+    const int32_t* gather = gather_rows ? perm : nullptr;
+    const void* ffn_in = gather_rows ? x : static_cast<const void*>(base + L.Xp);
 
     int early = -1;                // streamed mode: the expert requested before routing, if any
     if (sctx != nullptr) {
@@ -380,17 +387,18 @@ int layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const floa
     if (int rc = launch_route(c, x, W_g, gate_bias, idx, w, base + L.route, s)) return rc;
     if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[1], s));
     bool planned = false;          // resident mode: the work list of the one FFN launch may come from the batching kernel
-    if (int rc = launch_permute(c, x, idx, counts, offsets, perm, inv, base + L.Xp,
+    if (int rc = launch_permute(c, x, idx, counts, offsets, perm, inv, gather_rows ? nullptr : base + L.Xp,
                                 reinterpret_cast<int32_t*>(base + L.chunk_hist), s,
                                 sctx == nullptr ? reinterpret_cast<int32_t*>(base + L.ffn_plan) : nullptr,
-                                static_cast<int>(ffn_plan_tiles(c)), sctx == nullptr ? &planned : nullptr))
+                                static_cast<int>(ffn_plan_tiles(c)), sctx == nullptr ? &planned : nullptr,
+                                ffn_tile_rows(gather_rows)))
         return rc;
     if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[2], s));
 
     if (sctx == nullptr) {
-        if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, 0, c.E, W_packed, eb, A, base + L.H, ffn_out,
+        if (int rc = launch_expert_ffn(c, ffn_in, offsets, 0, c.E, W_packed, eb, A, base + L.H, ffn_out,
                                        reinterpret_cast<int32_t*>(base + L.ffn_plan), s, tev ? tev[3] : nullptr,
-                                       tev && up_only ? tev[2] : nullptr, row_map, planned))
+                                       tev && up_only ? tev[2] : nullptr, row_map, planned, gather))
             return rc;
         if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[4], s));
     } else {
@@ -432,8 +440,8 @@ int layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const floa
             // Everything this call needs is resident and the slots are laid out like a resident expert array:
             // one launch over all experts instead of one per expert.
             for (int pos = 0; pos < n_order; ++pos) MOE_HIP_CHECK(hipStreamWaitEvent(s, sctx->loaded[slot_of[pos]], 0));
-            if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, 0, c.E, sctx->dev_slots, eb, A, base + L.H, ffn_out,
-                                           reinterpret_cast<int32_t*>(base + L.ffn_plan), s, nullptr, nullptr, row_map))
+            if (int rc = launch_expert_ffn(c, ffn_in, offsets, 0, c.E, sctx->dev_slots, eb, A, base + L.H, ffn_out,
+                                           reinterpret_cast<int32_t*>(base + L.ffn_plan), s, nullptr, nullptr, row_map, false, gather))
                 return rc;
             for (int pos = 0; pos < n_order; ++pos)
                 if (int rc = record_release(sctx, slot_of[pos], s)) return rc;
@@ -454,8 +462,8 @@ int layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const floa
                 if (int rc = enqueue_load(sctx, e, slot)) return rc;
             }
             MOE_HIP_CHECK(hipStreamWaitEvent(s, sctx->loaded[slot], 0));   // also when kept: its load may still be running
-            if (int rc = launch_expert_ffn(c, base + L.Xp, offsets, e, 1, dst, eb, n_e, base + L.H, ffn_out,
-                                           reinterpret_cast<int32_t*>(base + L.ffn_plan), s, nullptr, nullptr, row_map))
+            if (int rc = launch_expert_ffn(c, ffn_in, offsets, e, 1, dst, eb, n_e, base + L.H, ffn_out,
+                                           reinterpret_cast<int32_t*>(base + L.ffn_plan), s, nullptr, nullptr, row_map, false, gather))
                 return rc;
             if (int rc = record_release(sctx, slot, s)) return rc;
         }

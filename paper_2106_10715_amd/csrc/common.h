@@ -75,7 +75,7 @@ size_t gate_packed_bytes(const moe_cfg& c);
 int launch_pack_gate(const moe_cfg& c, const void* Wg, void* packed, hipStream_t s);
 int launch_permute(const moe_cfg& c, const void* x, const int32_t* idx, int32_t* counts, int32_t* offsets,
                    int32_t* perm, int32_t* inv, void* Xp, int32_t* chunk_hist, hipStream_t s, int32_t* plan = nullptr,
-                   int plan_max_tiles = 0, bool* planned = nullptr);
+                   int plan_max_tiles = 0, bool* planned = nullptr, int plan_tile_rows = kTileM);
 // plan/planned: for short bf16 batches the kernel that batches the tokens also writes the work list of the expert
 // FFN launch over all experts that follows (room for plan_max_tiles row tiles) and sets *planned; the caller then
 // passes plan_ready to launch_expert_ffn.
@@ -93,7 +93,12 @@ int launch_pack(const moe_cfg& c, const void* Win, const void* Wgate, const void
 int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, int e_first, int e_count,
                       const void* W, size_t expert_stride_bytes, long max_rows, void* H, void* Yp, int32_t* plan,
                       hipStream_t s, hipEvent_t between = nullptr, hipEvent_t before_up = nullptr,
-                      const int32_t* row_map = nullptr, bool plan_ready = false);
+                      const int32_t* row_map = nullptr, bool plan_ready = false, const int32_t* gather = nullptr);
+// gather (bf16 only): Xp is then the token array x[T, d] itself and batched row r is its row gather[r] / k (gather = the
+// perm written by the batching step), so the batched copy of the activations need not exist; row tiles are then
+// ffn_tile_rows(true) rows high instead of ffn_tile_rows(false), and a work list written elsewhere (plan_ready) must
+// have been cut to that height.
+int ffn_tile_rows(bool gather);
 // row_map (bf16 only): row r of the batched order is written to row row_map[r] of Yp instead of row r, which
 // turns the down-projection's output into the layer's output when no weighting follows (see moe_layer_forward).
 // `plan`: ffn_plan_bytes(c) bytes of workspace, rewritten by every launch_expert_ffn (room for ffn_plan_tiles(c) row tiles).

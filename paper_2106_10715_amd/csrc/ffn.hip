@@ -24,6 +24,9 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kKC = 64;                 // reduction elements staged per pipeline step (4 MFMA k-steps)
+// Rows of a tile when the up-projection gathers its rows itself: a thread then holds one source offset per
+// 32-row block, which the registers allow up to seven blocks (eight accumulator blocks leave no room).
+constexpr int kGatherTileM = 224;
 
 __device__ inline float act_fn(float z, int act) {
     if (act == 0) return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
@@ -427,10 +430,14 @@ __device__ inline unsigned thread_id(int wave) {
 // to the last step) instead of being skipped, so every step issues the same loads.  Rows that are
 // clamped duplicates only produce output rows that are never stored (an output row depends on its own
 // input row only).
-template <bool GATED, int NF, int MBS, bool KEEP>
+// GATHER: A is not the batched row array but the token array it was gathered from, and row r of the batched
+// order is token gather[r] / gather_k of A (the batching of Section 6.2 done on the fly: the batched copy of the
+// activations is never written); every thread then keeps one byte offset per row block instead of two in all.
+template <bool GATED, int NF, int MBS, bool KEEP, bool GATHER = false>
 __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_t* __restrict__ A, int row_begin, int rows,
                                 const void* wave_base, uint16_t* __restrict__ C, int K, int N, int unit,
-                                bool active, int act, unsigned phase_key, int wave_s, const int32_t* __restrict__ row_map) {
+                                bool active, int act, unsigned phase_key, int wave_s, const int32_t* __restrict__ row_map,
+                                const int32_t* __restrict__ gather = nullptr, int gather_k = 1) {
     unsigned tid = thread_id(wave_s);
     const int lane = tid & 63;
     // every tile height gets its own copy of the loop bounds: shared ones would be computed once for all
@@ -446,6 +453,14 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
     const uint32_t a_first = static_cast<uint32_t>(row_begin + r0) * K * 2u + piece;
     const uint32_t a_last = static_cast<uint32_t>(row_begin + min((MBS - 1) * 32 + r0, rows - 1)) * K * 2u + piece;
     const uint32_t a_stride = 64u * K;          // 32 rows, in bytes
+    uint32_t a_off[GATHER ? MBS : 1];           // GATHER: this thread's source row of every block, as a byte offset from A
+    if constexpr (GATHER) {
+#pragma unroll
+        for (int mb = 0; mb < MBS; ++mb) {
+            const int row = row_begin + min(mb * 32 + r0, rows - 1);
+            a_off[mb] = static_cast<uint32_t>(gather[row] / gather_k) * K * 2u + piece;
+        }
+    }
 
     f32x16 acc[MBS][NF];
     // cleared in place, in the accumulation registers: a zero constant would be parked in 16 registers for all
@@ -475,9 +490,14 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
     // per-thread part is the same register for every block but the last
     auto fetch_a = [&](ARegs<MBS>& dst, int chunk) {
         const char* base = reinterpret_cast<const char*>(A) + static_cast<size_t>(chunk) * (kKC * 2);
+        if constexpr (GATHER) {
 #pragma unroll
-        for (int mb = 0; mb + 1 < MBS; ++mb) ld_pinned<0>(dst.v[mb], a_first, base + static_cast<size_t>(mb) * a_stride);
-        ld_pinned<0>(dst.v[MBS - 1], a_last, base);
+            for (int mb = 0; mb < MBS; ++mb) ld_pinned<0>(dst.v[mb], a_off[mb], base);
+        } else {
+#pragma unroll
+            for (int mb = 0; mb + 1 < MBS; ++mb) ld_pinned<0>(dst.v[mb], a_first, base + static_cast<size_t>(mb) * a_stride);
+            ld_pinned<0>(dst.v[MBS - 1], a_last, base);
+        }
     };
     auto fetch_b = [&](BFrags<NF>& dst, int chunk) {
         load_b<KEEP>(dst, static_cast<uint32_t>(chunk) * (kKS * 2048) + lane * 16, wave_base);
@@ -516,9 +536,12 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
         /* past the last step there is nothing left to prefetch: the loads still issue (the waits count   \
            them), but all lanes read the same 16 bytes, one cache line instead of a KiB per load */       \
         const uint32_t a_first_c = ci + AD > last ? 0u : a_first, a_last_c = ci + AD > last ? 0u : a_last; \
+        const uint32_t a_keep = ci + AD > last ? 0u : ~0u;                                                 \
         auto issue_a = [&](auto ic) {                                                                      \
             constexpr int mb = decltype(ic)::value;                                                        \
-            if constexpr (mb + 1 < MBS)                                                                    \
+            if constexpr (GATHER)                                                                          \
+                ld_pinned<0>(areg[((I) + AD) % AD].v[mb], a_off[mb] & a_keep, a_base);                     \
+            else if constexpr (mb + 1 < MBS)                                                               \
                 ld_pinned<0>(areg[((I) + AD) % AD].v[mb], a_first_c, a_base + static_cast<size_t>(mb) * a_stride); \
             else                                                                                           \
                 ld_pinned<0>(areg[((I) + AD) % AD].v[mb], a_last_c, a_base);                               \
@@ -671,12 +694,16 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
 // column groups.  Tiles of one expert then share its weight stream, and the column groups of a tile
 // share its activation tile, in that XCD's L2; groups of tiles are dealt to the queues in turn.  A
 // block whose own queue is empty helps with the others.
-template <bool GATED, int NF>
+// GATHER (up-projection only): A is the token array x and the rows of a tile are looked up through `gather`
+// (the permutation written by the batching step; row r is token gather[r] / gather_k); tiles then have at most
+// kGatherTileM rows.
+template <bool GATED, int NF, bool GATHER = false>
 __global__ __launch_bounds__(256) void ffn_mfma_kernel(const uint16_t* __restrict__ A, int32_t* __restrict__ plan,
                                                        int counter_base, int e_first, const char* __restrict__ W,
                                                        size_t expert_stride_bytes, size_t block_offset_bytes,
                                                        uint16_t* __restrict__ C, int K, int N, int act, int y_chunks,
-                                                       int mt_shift, const int32_t* __restrict__ row_map) {
+                                                       int mt_shift, const int32_t* __restrict__ row_map,
+                                                       const int32_t* __restrict__ gather, int gather_k) {
     __shared__ uint4 lds[2][kTileM * kLdsRow];     // 2 x 36 KiB activation tiles, padded rows
     __shared__ int sh_q, sh_x;
     const int tiles = plan[16];
@@ -740,29 +767,22 @@ __global__ __launch_bounds__(256) void ffn_mfma_kernel(const uint16_t* __restric
         const unsigned col_chunk = static_cast<unsigned>(block_y) >> ((GATED || NF == 2) ? 3 : 4);   // same for both unit widths
         const unsigned key = static_cast<unsigned>(e) * 37u + col_chunk;
         // weights of an expert with two row tiles or more are left in the L2 for its other tiles
-        if (tiles_of_expert >= kKeepFromTiles) {
-            switch ((rows + 31) >> 5) {
-                case 1: ffn_tile<GATED, NF, 1, true>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-                case 2: ffn_tile<GATED, NF, 2, true>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-                case 3: ffn_tile<GATED, NF, 3, true>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-                case 4: ffn_tile<GATED, NF, 4, true>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-                case 5: ffn_tile<GATED, NF, 5, true>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-                case 6: ffn_tile<GATED, NF, 6, true>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-                case 7: ffn_tile<GATED, NF, 7, true>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-                default: ffn_tile<GATED, NF, 8, true>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-            }
+        const bool keep = tiles_of_expert >= kKeepFromTiles;
+        const int blocks = min((rows + 31) >> 5, GATHER ? kGatherTileM / 32 : kTileM / 32);
+#define FFN_TILE(M, KP)                                                                                              \
+    ffn_tile<GATED, NF, M, KP, GATHER>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map, \
+                                       gather, gather_k)
+#define FFN_CASE(M)                                                                                                  \
+    case M:                                                                                                          \
+        if (keep) FFN_TILE(M, true); else FFN_TILE(M, false);                                                        \
+        break;
+        if constexpr (GATHER) {
+            switch (blocks) { FFN_CASE(1) FFN_CASE(2) FFN_CASE(3) FFN_CASE(4) FFN_CASE(5) FFN_CASE(6) default: if (keep) FFN_TILE(kGatherTileM / 32, true); else FFN_TILE(kGatherTileM / 32, false); break; }
         } else {
-            switch ((rows + 31) >> 5) {
-                case 1: ffn_tile<GATED, NF, 1, false>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-                case 2: ffn_tile<GATED, NF, 2, false>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-                case 3: ffn_tile<GATED, NF, 3, false>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-                case 4: ffn_tile<GATED, NF, 4, false>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-                case 5: ffn_tile<GATED, NF, 5, false>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-                case 6: ffn_tile<GATED, NF, 6, false>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-                case 7: ffn_tile<GATED, NF, 7, false>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-                default: ffn_tile<GATED, NF, 8, false>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map); break;
-            }
+            switch (blocks) { FFN_CASE(1) FFN_CASE(2) FFN_CASE(3) FFN_CASE(4) FFN_CASE(5) FFN_CASE(6) FFN_CASE(7) default: if (keep) FFN_TILE(8, true); else FFN_TILE(8, false); break; }
         }
+#undef FFN_CASE
+#undef FFN_TILE
     }
 }
 
@@ -837,7 +857,8 @@ __global__ __launch_bounds__(256) void copy_vec_kernel(const uint4* __restrict__
 
 }  // namespace
 
-size_t ffn_plan_tiles(const moe_cfg& c) { return static_cast<size_t>(c.T) * c.k / kTileM + c.E; }
+size_t ffn_plan_tiles(const moe_cfg& c) { return static_cast<size_t>(c.T) * c.k / kGatherTileM + c.E; }   // the lower of the two tile heights
+int ffn_tile_rows(bool gather) { return gather ? kGatherTileM : kTileM; }
 size_t ffn_plan_bytes(const moe_cfg& c) { return (kPlanHeader + 4 * ffn_plan_tiles(c)) * sizeof(int32_t); }
 
 int launch_pack(const moe_cfg& c, const void* Win, const void* Wgate, const void* Wout, void* packed, hipStream_t s) {
@@ -864,13 +885,16 @@ int launch_pack(const moe_cfg& c, const void* Win, const void* Wgate, const void
 
 int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, int e_first, int e_count,
                       const void* W, size_t expert_stride_bytes, long max_rows, void* H, void* Yp, int32_t* plan,
-                      hipStream_t s, hipEvent_t between, hipEvent_t before_up, const int32_t* row_map, bool plan_ready) {
+                      hipStream_t s, hipEvent_t between, hipEvent_t before_up, const int32_t* row_map, bool plan_ready,
+                      const int32_t* gather) {
     if (max_rows <= 0 || e_count <= 0) return MOE_OK;
     const size_t df = static_cast<size_t>(c.d) * c.f;
+    if (gather != nullptr && c.dtype != MOE_BF16) return fail(MOE_ERR_UNSUPPORTED, "gathered rows are a bf16 path");
     if (c.dtype == MOE_BF16) {
         // Work items: 8 queues x (groups of row tiles per queue) x (chunks of column groups) x 32; the
         // resident blocks take them until the queues are empty.
-        const long slots = max_rows / kTileM + e_count;                // upper bound of the number of row tiles
+        const int tile_m = ffn_tile_rows(gather != nullptr);
+        const long slots = max_rows / tile_m + e_count;                // upper bound of the number of row tiles
         if (slots > static_cast<long>(ffn_plan_tiles(c)))
             return fail(MOE_ERR_INVALID_ARG, "more row tiles (%ld) than the workspace plans for", slots);
         // Row tiles per group (4, 2 or 1): neighbouring tiles in the list belong to one expert when experts have
@@ -894,7 +918,7 @@ int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, 
         const int n_cu = info->compute_units;
         auto grid_for = [&](long items) { return dim3(static_cast<unsigned>(items < n_cu ? items : n_cu)); };
         if (!plan_ready) {          // else the kernel that batched the tokens has written the work list as well
-            hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, s, offsets, e_first, e_count, kTileM, plan,
+            hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, s, offsets, e_first, e_count, tile_m, plan,
                                c.T * c.k, static_cast<int>(ffn_plan_tiles(c)));
             MOE_LAUNCH_CHECK("ffn_plan_kernel");
         }
@@ -904,13 +928,20 @@ int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, 
         int yc = 0;
         long items = items_for((c.f / 32 + 3) / 4, yc);
         if (items > 0x7fffffffL) return fail(MOE_ERR_UNSUPPORTED, "too many work items for one launch (%ld)", items);
-        hipLaunchKernelGGL((ffn_mfma_kernel<true, 2>), grid_for(items), block, 0, s, static_cast<const uint16_t*>(Xp), plan, 0,
-                           e_first, static_cast<const char*>(W), expert_stride_bytes, size_t(0), static_cast<uint16_t*>(H),
-                           c.d, c.f, c.act, yc, mt_shift, static_cast<const int32_t*>(nullptr));
+        // (with `gather`, Xp is the token array and the kernel looks its rows up itself)
+        if (gather != nullptr)
+            hipLaunchKernelGGL((ffn_mfma_kernel<true, 2, true>), grid_for(items), block, 0, s, static_cast<const uint16_t*>(Xp), plan, 0,
+                               e_first, static_cast<const char*>(W), expert_stride_bytes, size_t(0), static_cast<uint16_t*>(H),
+                               c.d, c.f, c.act, yc, mt_shift, static_cast<const int32_t*>(nullptr), gather, c.k);
+        else
+            hipLaunchKernelGGL((ffn_mfma_kernel<true, 2>), grid_for(items), block, 0, s, static_cast<const uint16_t*>(Xp), plan, 0,
+                               e_first, static_cast<const char*>(W), expert_stride_bytes, size_t(0), static_cast<uint16_t*>(H),
+                               c.d, c.f, c.act, yc, mt_shift, static_cast<const int32_t*>(nullptr),
+                               static_cast<const int32_t*>(nullptr), 1);
         MOE_LAUNCH_CHECK("ffn_mfma_kernel<up>");
         if (between != nullptr) MOE_HIP_CHECK(hipEventRecord(between, s));
         // down-projection: narrow (32-column) units when wide ones would leave compute units idle
-        const long tiles_hint = (max_rows + kTileM - 1) / kTileM > e_count ? (max_rows + kTileM - 1) / kTileM : e_count;
+        const long tiles_hint = (max_rows + tile_m - 1) / tile_m > e_count ? (max_rows + tile_m - 1) / tile_m : e_count;
         // (only while the experts are likely to have a single tile each, mean rows up to 224, and their items are
         // bound by the weight stream: on 256-row tiles, and once experts spill into second tiles, the narrow unit's
         // second LDS read per MFMA costs more than the idle compute units do; measured on 8 experts: 128 rows per
@@ -921,11 +952,11 @@ int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, 
         if (narrow)
             hipLaunchKernelGGL((ffn_mfma_kernel<false, 1>), grid_for(items), block, 0, s, static_cast<const uint16_t*>(H), plan, 8,
                                e_first, static_cast<const char*>(W), expert_stride_bytes, down_off, static_cast<uint16_t*>(Yp),
-                               c.f, c.d, c.act, yc, mt_shift, row_map);
+                               c.f, c.d, c.act, yc, mt_shift, row_map, static_cast<const int32_t*>(nullptr), 1);
         else
             hipLaunchKernelGGL((ffn_mfma_kernel<false, 2>), grid_for(items), block, 0, s, static_cast<const uint16_t*>(H), plan, 8,
                                e_first, static_cast<const char*>(W), expert_stride_bytes, down_off, static_cast<uint16_t*>(Yp),
-                               c.f, c.d, c.act, yc, mt_shift, row_map);
+                               c.f, c.d, c.act, yc, mt_shift, row_map, static_cast<const int32_t*>(nullptr), 1);
         MOE_LAUNCH_CHECK("ffn_mfma_kernel<down>");
         return MOE_OK;
     }
