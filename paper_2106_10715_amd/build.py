@@ -26,7 +26,9 @@ def _hipcc() -> str:
 
 # ffn.hip spells out its software pipeline (loads first, LDS reads one k-step ahead of the MFMAs); the
 # machine scheduler would fold that back into load-use pairs to save registers, so it is switched off there.
-EXTRA = {"ffn.hip": ["-mllvm", "-enable-misched=false"]}
+# Its work-queue atomics are issued by one lane whose answer is wanted later (it arrives under other work); the atomic
+# optimizer would rewrite them into a wave reduction whose broadcast waits for the answer on the spot.
+EXTRA = {"ffn.hip": ["-mllvm", "-enable-misched=false", "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"]}
 # The MFMA kernels of ffn.hip keep loads in flight in registers the compiler knows nothing about and count
 # the outstanding loads by hand.  Spill code inside such a region could save a register before its load
 # has landed, and its own memory operations would be counted as if they were the kernel's.  The source

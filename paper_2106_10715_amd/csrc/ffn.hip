@@ -425,6 +425,86 @@ __device__ inline unsigned thread_id(int wave) {
     return static_cast<unsigned>(wave) * 64u + lane;
 }
 
+// ---- work items.  A launch's items are positions of 8 queues (one per XCD; see ffn_mfma_kernel); everything a
+// block needs to take one and to find out what it means, all of it uniform (scalar registers):
+struct ItemQueue {
+    unsigned* counters;            // next position of each queue
+    unsigned total_q, home;        // positions per queue; this block's own queue
+    const int4* tile_list;         // (expert, first row, rows, row tiles of the expert) per row tile
+    int tiles, y_chunks, mt_shift;
+    const char* W;                 // packed weights of expert e_first (+ block_offset_bytes: the up or the down block)
+    size_t expert_stride_bytes, block_offset_bytes;
+    int e_first;
+};
+struct Item {
+    bool real;                     // false: padding of the queue (past the last tile or column group)
+    int e, row_begin, rows, tiles_of_expert, block_y;
+};
+
+__device__ inline Item decode_item(const ItemQueue& Q, unsigned q, unsigned xcd, int units) {
+    const unsigned ny = 32u >> Q.mt_shift;     // column groups per run of 32; 1 << mt_shift row tiles
+    const unsigned yg = q & (ny - 1u), mt = (q / ny) & ((1u << Q.mt_shift) - 1u), rest = q >> 5;
+    const unsigned y_chunk = rest % static_cast<unsigned>(Q.y_chunks), tile_group = rest / static_cast<unsigned>(Q.y_chunks);
+    const int slot = static_cast<int>((((tile_group << 3) + xcd) << Q.mt_shift) + mt);
+    Item it;
+    it.block_y = static_cast<int>(y_chunk * ny + yg);
+    it.real = slot < Q.tiles && it.block_y * 4 < units;
+    it.e = it.row_begin = it.rows = it.tiles_of_expert = 0;
+    if (it.real) {
+        // the same for all lanes, and written by an earlier kernel: read through the scalar cache
+        typedef int i32x4 __attribute__((ext_vector_type(4)));
+        typedef const __attribute__((address_space(4))) i32x4 constant_i32x4;
+        const i32x4 tile = ((constant_i32x4*)Q.tile_list)[slot];
+        it.e = __builtin_amdgcn_readfirstlane(tile.x);
+        it.row_begin = __builtin_amdgcn_readfirstlane(tile.y);
+        it.rows = __builtin_amdgcn_readfirstlane(tile.z);
+        it.tiles_of_expert = __builtin_amdgcn_readfirstlane(tile.w);
+    }
+    return it;
+}
+
+// Start of a wave's fragment stream in an item and the key that fixes where its sweep over the reduction dimension
+// starts: the sweep starts at a step that depends on the expert and on the chunk of 8 column groups only, so blocks that
+// share a weight stream or an activation tile walk it together; neighbouring chunks are one step apart (measured:
+// far-apart chunks fetch the activation tile again, chunks in step collide on their weight streams), other experts
+// anywhere.  The same for all lanes, so the address is handed over in scalar registers.
+template <bool GATED, int NF>
+__device__ inline const void* wave_stream(const ItemQueue& Q, int e, int block_y, int wave, int units, int K, unsigned& key) {
+    const int unit = block_y * 4 + wave;
+    const int u = unit < units ? unit : units - 1;     // a wave past the last unit recomputes the last one, stores nothing
+    const int steps16 = K / 16;
+    // fragment pair index and which half of the pair this wave reads
+    const int pair = (GATED || NF == 2) ? u : (u >> 1);
+    const int half = (GATED || NF == 2) ? 0 : (u & 1);
+    const char* wb = Q.W + static_cast<size_t>(e - Q.e_first) * Q.expert_stride_bytes + Q.block_offset_bytes +
+                     (static_cast<size_t>(pair) * steps16 * 128 + half * 64) * 16;
+    const uintptr_t wbi = reinterpret_cast<uintptr_t>(wb);
+    const uint32_t wb_lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(wbi))));
+    const uint32_t wb_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(wbi >> 32))));
+    const unsigned col_chunk = static_cast<unsigned>(block_y) >> ((GATED || NF == 2) ? 3 : 4);   // same for both unit widths
+    key = static_cast<unsigned>(e) * 37u + col_chunk;
+    return reinterpret_cast<const void*>((static_cast<uintptr_t>(wb_hi) << 32) | static_cast<uintptr_t>(wb_lo));
+}
+
+// Thread 0 takes the next position: first from the block's own queue, and when that is empty from the others.
+// The first attempt is split from the rest so that its answer can arrive under other work.
+__device__ inline unsigned take_first(const ItemQueue& Q) { return atomicAdd(&Q.counters[Q.home], 1u); }
+__device__ inline void take_finish(const ItemQueue& Q, unsigned v, int* sh_q, int* sh_x) {
+    int got = -1;
+    unsigned x = Q.home;
+    if (v < Q.total_q) {
+        got = static_cast<int>(v);
+    } else {
+        for (unsigned i = 1; i < 8u; ++i) {
+            x = (Q.home + i) & 7u;
+            const unsigned w = atomicAdd(&Q.counters[x], 1u);
+            if (w < Q.total_q) { got = static_cast<int>(w); break; }
+        }
+    }
+    *sh_q = got;
+    *sh_x = static_cast<int>(x);
+}
+
 // One tile of MBS 32-row blocks: the whole reduction loop and the epilogue.
 // Loads past the end are clamped to valid addresses (rows to the last row of the tile, pipeline steps
 // to the last step) instead of being skipped, so every step issues the same loads.  Rows that are
@@ -437,7 +517,8 @@ template <bool GATED, int NF, int MBS, bool KEEP, bool GATHER = false>
 __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_t* __restrict__ A, int row_begin, int rows,
                                 const void* wave_base, uint16_t* __restrict__ C, int K, int N, int unit,
                                 bool active, int act, unsigned phase_key, int wave_s, const int32_t* __restrict__ row_map,
-                                const int32_t* __restrict__ gather = nullptr, int gather_k = 1) {
+                                const int32_t* __restrict__ gather, int gather_k, const ItemQueue& Q, int units, int* sh_q,
+                                int* sh_x, int h_rows) {
     unsigned tid = thread_id(wave_s);
     const int lane = tid & 63;
     // every tile height gets its own copy of the loop bounds: shared ones would be computed once for all
@@ -450,9 +531,16 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
     // of the last block re-read the tile's last row.
     const int r0 = tid >> 3;
     const uint32_t piece = 16u * (tid & 7);
-    const uint32_t a_first = static_cast<uint32_t>(row_begin + r0) * K * 2u + piece;
-    const uint32_t a_last = static_cast<uint32_t>(row_begin + min((MBS - 1) * 32 + r0, rows - 1)) * K * 2u + piece;
-    const uint32_t a_stride = 64u * K;          // 32 rows, in bytes
+    // Layout of A.  The up-projection reads row-major rows (K elements each).  The down-projection reads the
+    // intermediate H, which only these two kernels see and which is therefore kept in the order they touch it:
+    // [chunk of 64 columns][row][64 columns], all h_rows rows of a chunk back to back, so that a tile's rows of one
+    // chunk are one contiguous run, for the up-projection's stores (scattered 256-byte pieces cost the memory far
+    // more than their bytes) as for these loads.
+    const uint32_t a_row_bytes = GATED ? static_cast<uint32_t>(K) * 2u : static_cast<uint32_t>(kKC * 2);
+    const size_t a_chunk_bytes = GATED ? static_cast<size_t>(kKC * 2) : static_cast<size_t>(h_rows) * (kKC * 2);
+    const uint32_t a_first = static_cast<uint32_t>(row_begin + r0) * a_row_bytes + piece;
+    const uint32_t a_last = static_cast<uint32_t>(row_begin + min((MBS - 1) * 32 + r0, rows - 1)) * a_row_bytes + piece;
+    const uint32_t a_stride = 32u * a_row_bytes;        // 32 rows, in bytes
     uint32_t a_off[GATHER ? MBS : 1];           // GATHER: this thread's source row of every block, as a byte offset from A
     if constexpr (GATHER) {
 #pragma unroll
@@ -489,7 +577,7 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
     // the per-block and per-step parts of the address are uniform: they go into the scalar base, and the
     // per-thread part is the same register for every block but the last
     auto fetch_a = [&](ARegs<MBS>& dst, int chunk) {
-        const char* base = reinterpret_cast<const char*>(A) + static_cast<size_t>(chunk) * (kKC * 2);
+        const char* base = reinterpret_cast<const char*>(A) + static_cast<size_t>(chunk) * a_chunk_bytes;
         if constexpr (GATHER) {
 #pragma unroll
             for (int mb = 0; mb < MBS; ++mb) ld_pinned<0>(dst.v[mb], a_off[mb], base);
@@ -532,7 +620,7 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
     {                                                                                                      \
         const int ci = c + (I);                                                                            \
         const char* a_base = reinterpret_cast<const char*>(A) +                                            \
-                             static_cast<size_t>(at(min(ci + AD, last))) * (kKC * 2);                      \
+                             static_cast<size_t>(at(min(ci + AD, last))) * a_chunk_bytes;                  \
         /* past the last step there is nothing left to prefetch: the loads still issue (the waits count   \
            them), but all lanes read the same 16 bytes, one cache line instead of a KiB per load */       \
         const uint32_t a_first_c = ci + AD > last ? 0u : a_first, a_last_c = ci + AD > last ? 0u : a_last; \
@@ -585,6 +673,17 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
         for (int mb = 0; mb < MBS; ++mb) asm volatile("" : : "v"(areg[i].v[mb]));
     __syncthreads();                            // the last LDS reads are done before the epilogue reuses the LDS
     tid = thread_id(wave_s);                    // rebuilt: the first copy need not survive the main loop
+    // The block's next work item is taken now, by thread 0: the queue's answer arrives while the output tile is
+    // filled, is published with the barrier that follows the filling, and lets every wave request the first weights
+    // of its next item before it stores the tile, so that they are in the L2 (and the memory system has had this
+    // compute unit's requests) by the time the next item's own first loads ask for them.  An item is taken only a
+    // few microseconds before the block turns to it, so the balance of the queues is what it was.
+    unsigned taken = 0u;
+    if (tid == 0) taken = take_first(Q);
+    constexpr int kWarm = kKS * (GATED ? 2 : NF);       // 16-byte pieces per lane of one pipeline step of this wave's stream
+    u32x4 warm[kWarm];
+#pragma unroll
+    for (int i = 0; i < kWarm; ++i) warm[i] = u32x4{0u, 0u, 0u, 0u};
     // Epilogue through LDS (the activation buffers are free now).  The weight fragment is the first MFMA
     // operand and the activation fragment the second, so the accumulators hold the transposed tile: lane l
     // has token row l%32 of its row block and, in v = 4g..4g+3, the four neighbouring output columns
@@ -601,6 +700,21 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
     static_assert(kRowsPerPass * kTileRowBytes <= static_cast<int>(sizeof(lds)), "epilogue tile must fit the LDS buffers");
     const int wave = wave_s;
     const int row_in = (tid & 31), col_in = 4 * ((tid & 63) >> 5);
+    // the first step of this wave's weight stream in the block's next item (plain loads: they stay in the L2)
+    auto warm_next = [&]() {
+        const int nq = __builtin_amdgcn_readfirstlane(*sh_q);
+        if (nq < 0) return;
+        const Item nx = decode_item(Q, static_cast<unsigned>(nq), static_cast<unsigned>(__builtin_amdgcn_readfirstlane(*sh_x)), units);
+        if (!nx.real) return;
+        unsigned nkey;
+        const char* nw = static_cast<const char*>(wave_stream<GATED, NF>(Q, nx.e, nx.block_y, wave_s, units, K, nkey));
+        // (addressed as global memory, so that the loads return in order with the other global loads and the stores
+        // that follow wait for their own operands only)
+        typedef const __attribute__((address_space(1))) u32x4 global_u32x4;
+        global_u32x4* src = (global_u32x4*)(nw + static_cast<size_t>(nkey % static_cast<unsigned>(chunks)) * (kKS * 2048)) + (tid & 63);
+#pragma unroll
+        for (int i = 0; i < kWarm; ++i) warm[i] = src[(GATED || NF == 2) ? i * 64 : i * 128];
+    };
 #pragma unroll
     for (int p0 = 0; p0 < MBS * 32; p0 += kRowsPerPass) {
         if (p0 > 0) __syncthreads();                    // the previous pass has been stored
@@ -632,12 +746,17 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
         };
         if (!GATED || act == 0) fill(std::true_type{});
         else fill(std::false_type{});
+        if (p0 == 0 && tid == 0) take_finish(Q, taken, sh_q, sh_x);
         __syncthreads();
         const int seg = (tid % kLanesPerRow) * 8;       // first of this lane's 8 columns inside the block
         const int src_wave = seg / W;
         const int out_unit = unit - wave + src_wave;            // unit of the wave that produced them
         if (out_unit < N / W) {
-            uint16_t* cbase = C + static_cast<size_t>(out_unit) * W + (seg % W);
+            // first of this lane's 8 columns, and the distance between rows, in elements: row-major output, or
+            // (the up-projection's) the chunked order of H described above
+            const int col = out_unit * W + (seg % W);
+            uint16_t* cbase = GATED ? C + static_cast<size_t>(col >> 6) * h_rows * kKC + (col & (kKC - 1)) : C + col;
+            const size_t c_row_elems = GATED ? static_cast<size_t>(kKC) : static_cast<size_t>(N);
             // All pieces of the pass are read from the tile (and their output rows looked up) before the first
             // is stored: one LDS and one look-up latency per pass instead of one per piece.
             //   row_map: where each row of the batched order goes (the layer's output rows, when the rows
@@ -654,6 +773,7 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
                     out_row[i] = row_map != nullptr ? row_map[row] : row;
                 }
             }
+            if (p0 == 0) warm_next();
 #pragma unroll
             for (int i = 0; i < kPieces; ++i) {
                 if (i * kRowsPerIter < MBS * 32 - p0) {
@@ -663,11 +783,16 @@ __device__ inline void ffn_tile(uint4 (&lds)[2][kTileM * kLdsRow], const uint16_
                     // (5 % of the layer's time at 128 tokens per expert)
                     if (p0 + r < rows)
                         __builtin_nontemporal_store(u32x4{val[i].x, val[i].y, val[i].z, val[i].w},
-                                                    reinterpret_cast<u32x4*>(cbase + static_cast<size_t>(out_row[i]) * N));
+                                                    reinterpret_cast<u32x4*>(cbase + static_cast<size_t>(out_row[i]) * c_row_elems));
                 }
             }
+        } else if (p0 == 0) {
+            warm_next();
         }
     }
+    // the requested pieces are only wanted in the cache; their registers are given up once they have arrived
+#pragma unroll
+    for (int i = 0; i < kWarm; ++i) asm volatile("" : : "v"(warm[i]));
 }
 
 // The work list of a launch is written by ffn_plan_block (ffn_plan.h): here as a kernel of its own.
@@ -703,75 +828,52 @@ __global__ __launch_bounds__(256) void ffn_mfma_kernel(const uint16_t* __restric
                                                        size_t expert_stride_bytes, size_t block_offset_bytes,
                                                        uint16_t* __restrict__ C, int K, int N, int act, int y_chunks,
                                                        int mt_shift, const int32_t* __restrict__ row_map,
-                                                       const int32_t* __restrict__ gather, int gather_k) {
+                                                       const int32_t* __restrict__ gather, int gather_k, int h_rows) {
     __shared__ uint4 lds[2][kTileM * kLdsRow];     // 2 x 36 KiB activation tiles, padded rows
     __shared__ int sh_q, sh_x;
-    const int tiles = plan[16];
+    ItemQueue Q;
+    Q.tiles = plan[16];
+    Q.y_chunks = y_chunks;
+    Q.mt_shift = mt_shift;
     const unsigned per_group = 8u << mt_shift;
-    const unsigned total_q = (static_cast<unsigned>(tiles) + per_group - 1u) / per_group * static_cast<unsigned>(y_chunks) * 32u;
-    const int4* tile_list = reinterpret_cast<const int4*>(plan + kPlanHeader);
-    unsigned* counters = reinterpret_cast<unsigned*>(plan) + counter_base;
-    const unsigned home = blockIdx.x & 7u;
+    Q.total_q = (static_cast<unsigned>(Q.tiles) + per_group - 1u) / per_group * static_cast<unsigned>(y_chunks) * 32u;
+    Q.tile_list = reinterpret_cast<const int4*>(plan + kPlanHeader);
+    Q.counters = reinterpret_cast<unsigned*>(plan) + counter_base;
+    Q.home = blockIdx.x & 7u;
+    Q.W = W;
+    Q.expert_stride_bytes = expert_stride_bytes;
+    Q.block_offset_bytes = block_offset_bytes;
+    Q.e_first = e_first;
     const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
-    for (bool first = true;; first = false) {
-        if (!first) __syncthreads();               // the previous item is done with the LDS and with sh_q
-        if (thread_id(wave) == 0) {
-            int got = -1;
-            unsigned x = home;
-            for (unsigned i = 0; i < 8u; ++i) {
-                x = (home + i) & 7u;
-                const unsigned v = atomicAdd(&counters[x], 1u);
-                if (v < total_q) { got = static_cast<int>(v); break; }
-            }
-            sh_q = got;
-            sh_x = static_cast<int>(x);
-        }
+    // an item taken with nothing to do meanwhile: the first one, and the one after a padding position
+    auto take_now = [&]() {
+        __syncthreads();                           // everybody has read the previous position
+        if (thread_id(wave) == 0) take_finish(Q, take_first(Q), &sh_q, &sh_x);
         __syncthreads();
+    };
+    take_now();
+    for (;;) {
         if (sh_q < 0) return;                      // every queue is empty (uniform for the block)
         // The tile code below is compiled for eight tile heights; values that do not change from item to
         // item would be hoisted out of this loop and held in registers across all of them.  The inputs
         // are made opaque per iteration instead.
         int Kl = K, Nl = N;
         asm volatile("" : "+s"(Kl), "+s"(Nl));
-        const unsigned xcd = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(sh_x));
-        const unsigned q = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(sh_q));
-        const unsigned ny = 32u >> mt_shift;       // column groups per run of 32; 1 << mt_shift row tiles
-        const unsigned yg = q & (ny - 1u), mt = (q / ny) & ((1u << mt_shift) - 1u), rest = q >> 5;
-        const unsigned y_chunk = rest % static_cast<unsigned>(y_chunks), tile_group = rest / static_cast<unsigned>(y_chunks);
-        const int slot = static_cast<int>((((tile_group << 3) + xcd) << mt_shift) + mt);
-        const int block_y = static_cast<int>(y_chunk * ny + yg);
         const int units = Nl / (32 * (GATED ? 1 : NF));
-        if (slot >= tiles || block_y * 4 >= units) continue;   // past the last tile or column group (uniform)
-        const int4 tile = tile_list[slot];         // the same for all lanes: kept in scalar registers
-        const int e = __builtin_amdgcn_readfirstlane(tile.x), row_begin = __builtin_amdgcn_readfirstlane(tile.y),
-                  rows = __builtin_amdgcn_readfirstlane(tile.z), tiles_of_expert = __builtin_amdgcn_readfirstlane(tile.w);
-
-        const int unit = block_y * 4 + wave;
+        const Item it = decode_item(Q, static_cast<unsigned>(__builtin_amdgcn_readfirstlane(sh_q)),
+                                    static_cast<unsigned>(__builtin_amdgcn_readfirstlane(sh_x)), units);
+        if (!it.real) { take_now(); continue; }    // past the last tile or column group (uniform)
+        const int e = it.e, row_begin = it.row_begin, rows = it.rows, tiles_of_expert = it.tiles_of_expert;
+        const int unit = it.block_y * 4 + wave;
         const bool active = unit < units;          // a wave past the last unit recomputes the last one, stores nothing
-        const int u = active ? unit : units - 1;
-        const int steps16 = Kl / 16;
-        // fragment pair index and which half of the pair this wave reads
-        const int pair = (GATED || NF == 2) ? u : (u >> 1);
-        const int half = (GATED || NF == 2) ? 0 : (u & 1);
-        // start of this wave's fragment stream; the same for all lanes, so it is handed over in scalar registers
-        const char* wb = W + static_cast<size_t>(e - e_first) * expert_stride_bytes + block_offset_bytes +
-                         (static_cast<size_t>(pair) * steps16 * 128 + half * 64) * 16;
-        const uintptr_t wbi = reinterpret_cast<uintptr_t>(wb);
-        const uint32_t wb_lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(wbi))));
-        const uint32_t wb_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(wbi >> 32))));
-        const void* wave_w = reinterpret_cast<const void*>((static_cast<uintptr_t>(wb_hi) << 32) | static_cast<uintptr_t>(wb_lo));
-        // The sweep over the reduction dimension starts at a step that depends on the expert and on the
-        // chunk of 8 column groups only: blocks that share a weight stream or an activation tile walk it
-        // together; neighbouring chunks are one step apart (measured: far-apart chunks fetch the activation
-        // tile again, chunks in step collide on their weight streams), other experts anywhere.
-        const unsigned col_chunk = static_cast<unsigned>(block_y) >> ((GATED || NF == 2) ? 3 : 4);   // same for both unit widths
-        const unsigned key = static_cast<unsigned>(e) * 37u + col_chunk;
+        unsigned key;
+        const void* wave_w = wave_stream<GATED, NF>(Q, e, it.block_y, wave, units, Kl, key);
         // weights of an expert with two row tiles or more are left in the L2 for its other tiles
         const bool keep = tiles_of_expert >= kKeepFromTiles;
         const int blocks = min((rows + 31) >> 5, GATHER ? kGatherTileM / 32 : kTileM / 32);
 #define FFN_TILE(M, KP)                                                                                              \
     ffn_tile<GATED, NF, M, KP, GATHER>(lds, A, row_begin, rows, wave_w, C, Kl, Nl, unit, active, act, key, wave, row_map, \
-                                       gather, gather_k)
+                                       gather, gather_k, Q, units, &sh_q, &sh_x, h_rows)
 #define FFN_CASE(M)                                                                                                  \
     case M:                                                                                                          \
         if (keep) FFN_TILE(M, true); else FFN_TILE(M, false);                                                        \
@@ -783,6 +885,7 @@ __global__ __launch_bounds__(256) void ffn_mfma_kernel(const uint16_t* __restric
         }
 #undef FFN_CASE
 #undef FFN_TILE
+        __syncthreads();                           // the tile has been read out of the LDS; the next position is in sh_q
     }
 }
 
@@ -932,12 +1035,12 @@ int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, 
         if (gather != nullptr)
             hipLaunchKernelGGL((ffn_mfma_kernel<true, 2, true>), grid_for(items), block, 0, s, static_cast<const uint16_t*>(Xp), plan, 0,
                                e_first, static_cast<const char*>(W), expert_stride_bytes, size_t(0), static_cast<uint16_t*>(H),
-                               c.d, c.f, c.act, yc, mt_shift, static_cast<const int32_t*>(nullptr), gather, c.k);
+                               c.d, c.f, c.act, yc, mt_shift, static_cast<const int32_t*>(nullptr), gather, c.k, c.T * c.k);
         else
             hipLaunchKernelGGL((ffn_mfma_kernel<true, 2>), grid_for(items), block, 0, s, static_cast<const uint16_t*>(Xp), plan, 0,
                                e_first, static_cast<const char*>(W), expert_stride_bytes, size_t(0), static_cast<uint16_t*>(H),
                                c.d, c.f, c.act, yc, mt_shift, static_cast<const int32_t*>(nullptr),
-                               static_cast<const int32_t*>(nullptr), 1);
+                               static_cast<const int32_t*>(nullptr), 1, c.T * c.k);
         MOE_LAUNCH_CHECK("ffn_mfma_kernel<up>");
         if (between != nullptr) MOE_HIP_CHECK(hipEventRecord(between, s));
         // down-projection: narrow (32-column) units when wide ones would leave compute units idle
@@ -952,11 +1055,11 @@ int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, 
         if (narrow)
             hipLaunchKernelGGL((ffn_mfma_kernel<false, 1>), grid_for(items), block, 0, s, static_cast<const uint16_t*>(H), plan, 8,
                                e_first, static_cast<const char*>(W), expert_stride_bytes, down_off, static_cast<uint16_t*>(Yp),
-                               c.f, c.d, c.act, yc, mt_shift, row_map, static_cast<const int32_t*>(nullptr), 1);
+                               c.f, c.d, c.act, yc, mt_shift, row_map, static_cast<const int32_t*>(nullptr), 1, c.T * c.k);
         else
             hipLaunchKernelGGL((ffn_mfma_kernel<false, 2>), grid_for(items), block, 0, s, static_cast<const uint16_t*>(H), plan, 8,
                                e_first, static_cast<const char*>(W), expert_stride_bytes, down_off, static_cast<uint16_t*>(Yp),
-                               c.f, c.d, c.act, yc, mt_shift, row_map, static_cast<const int32_t*>(nullptr), 1);
+                               c.f, c.d, c.act, yc, mt_shift, row_map, static_cast<const int32_t*>(nullptr), 1, c.T * c.k);
         MOE_LAUNCH_CHECK("ffn_mfma_kernel<down>");
         return MOE_OK;
     }
