@@ -108,7 +108,10 @@ int moe_pack_gate(const moe_cfg* cfg, const void* W_g, void* gate_packed, void* 
  * Gate (Sections 2.1, 2.3): logits L = x W_g (+ gate_bias); per token the k largest logits, slot j
  * ordered by descending logit, every tie resolved to the lower expert index; combine weights per
  * cfg->renorm.  The selection equals the one exact arithmetic on the stored inputs would make: tokens
- * whose fp32 logits are closer than the fp32 error bound are re-evaluated in fp64 inside the kernel.
+ * whose fp32 logits are closer than the fp32 error bound are re-evaluated inside the kernel from exact
+ * products, in fp64 and, if that still leaves candidates closer than its rounding error, in twice that
+ * precision (value + error term), which represents the sums exactly for inputs of comparable magnitude:
+ * columns whose exact projections are equal tie, and the tie goes to the lower expert index.
  *   x [T, d]: device, dtype.  W_g: device, the matrix [d, E] in dtype or, with cfg->gate_packed, the block
  *   written by moe_pack_gate.   gate_bias [E]: device fp32, or NULL.
  *   idx [T, k] int32, w [T, k] fp32: device, written.

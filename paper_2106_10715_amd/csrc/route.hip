@@ -4,11 +4,14 @@
 //
 // The selection must be the one exact arithmetic would make.  The kernel therefore accumulates
 // in fp32 with a summation order whose rounding error has a small rigorous bound, compares the gaps
-// between the k+1 best logits with that bound, and re-evaluates in fp64 only the tokens that are
-// too close to call (products of two bf16 or two fp32 values are exact in fp64).
+// between the k+1 best logits with that bound, and re-evaluates only the tokens that are too close to
+// call: products of two bf16 or two fp32 values are exact in fp64, and their sum is carried in two doubles
+// (value and rounding error), which holds it exactly for any inputs of comparable magnitude, so that
+// columns whose exact projections tie do tie.
 #include "common.h"
 
 #include <atomic>
+#include <type_traits>
 
 namespace moe {
 namespace {
@@ -22,29 +25,51 @@ constexpr int kSel = 9;        // k + 1 <= 9 ranks are looked at
 __device__ inline float ldf(const float* p, size_t i) { return p[i]; }
 __device__ inline float ldf(const __bf16* p, size_t i) { return static_cast<float>(p[i]); }
 
-// (value, expert) order of the gate: larger logit first, equal logits -> lower expert index first.
-__device__ inline bool before(double va, int ea, double vb, int eb) { return va > vb || (va == vb && ea < eb); }
+// (value, expert) order of the gate: larger logit first, equal logits -> lower expert index first.  A logit is a
+// pair (v, l) whose sum is its value, |l| at most half a unit in the last place of v (l = 0 for logits that were
+// not re-evaluated), so pairs compare like their values, part by part.
+__device__ inline bool before(double va, double la, int ea, double vb, double lb, int eb) {
+    return va > vb || (va == vb && (la > lb || (la == lb && ea < eb)));
+}
+
+// Sums in twice the working precision for the re-evaluated logits: the products of two stored values (at most 24
+// significant bits each) are exact in fp64, every addition keeps its rounding error (which two floating-point
+// numbers always represent exactly) in a second double, and the errors are added up there.  As long as the exact
+// sum fits some hundred bits (it does unless the inputs span more than 2^50 in magnitude) the pair holds it without
+// any rounding, whatever the order of the terms: columns whose exact projections are equal give identical pairs,
+// and a tie is a tie.
+__device__ inline void dd_add(double& hi, double& lo, double h2, double l2) {
+    const double sum = hi + h2, bb = sum - hi;
+    lo += ((hi - (sum - bb)) + (h2 - bb)) + l2;
+    hi = sum;
+}
+__device__ inline void dd_add_product(double& hi, double& lo, double x, double w) { dd_add(hi, lo, x * w, 0.0); }
+__device__ inline void dd_normalise(double& hi, double& lo) {
+    const double sum = hi + lo, bb = sum - hi;
+    lo = (hi - (sum - bb)) + (lo - bb);
+    hi = sum;
+}
 
 // The kk best of the wave's candidates, in order.  Lane `eg` owns experts eg + 64 i (i < kNE) when
 // `owner`; every lane receives the same result.
-__device__ inline void wave_topk(const double (&lv)[kNE], int eg, bool owner, int E, int kk,
+__device__ __attribute__((always_inline)) inline void wave_topk(const double (&lv)[kNE], const double (&ll)[kNE], int eg, bool owner, int E, int kk,
                                  double (&outv)[kSel], int (&oute)[kSel]) {
     unsigned taken = 0;
 #pragma unroll
     for (int r = 0; r < kSel; ++r) {
         if (r < kk) {
-            double v = -INFINITY;
+            double v = -INFINITY, l = 0.0;
             int e = 0x7fffffff;
 #pragma unroll
             for (int i = 0; i < kNE; ++i) {
                 const int ei = eg + 64 * i;
-                if (owner && ei < E && !((taken >> i) & 1u) && before(lv[i], ei, v, e)) { v = lv[i]; e = ei; }
+                if (owner && ei < E && !((taken >> i) & 1u) && before(lv[i], ll[i], ei, v, l, e)) { v = lv[i]; l = ll[i]; e = ei; }
             }
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) {
-                const double ov = __shfl_xor(v, off);
+                const double ov = __shfl_xor(v, off), ol = __shfl_xor(l, off);
                 const int oe = __shfl_xor(e, off);
-                if (before(ov, oe, v, e)) { v = ov; e = oe; }
+                if (before(ov, ol, oe, v, l, e)) { v = ov; l = ol; e = oe; }
             }
             outv[r] = v;
             oute[r] = e;
@@ -55,7 +80,7 @@ __device__ inline void wave_topk(const double (&lv)[kNE], int eg, bool owner, in
 
 // Combine weights of one token from its ranked logits, written by lane 0.  lv: this lane's logits of
 // the experts it owns (only read for the full-softmax denominator).
-__device__ inline void emit_token(const double (&lv)[kNE], const double (&sv)[kSel], const int (&se)[kSel], int eg, bool owner,
+__device__ __attribute__((always_inline)) inline void emit_token(const double (&lv)[kNE], const double (&sv)[kSel], const int (&se)[kSel], int eg, bool owner,
                                   int E, int k, int renorm, int lane, int32_t* __restrict__ idx_row, float* __restrict__ w_row) {
     float wj[kSel];
     float denom = 0.f;
@@ -88,9 +113,10 @@ __device__ inline void emit_token(const double (&lv)[kNE], const double (&sv)[kS
 // Sign-bit gate (the gate of Section 2.3 read as a hashing function): column j of the projection gives
 // bit j of the expert id, set when the projection is positive.  Lane j < bits holds projection j in
 // lv[0].  gap = the smallest |projection| (how close the token is to a boundary), vmax = the largest.
-__device__ inline void sign_bits(const double (&lv)[kNE], int eg, bool owner, int bits, int& code, double& gap, double& vmax) {
+__device__ __attribute__((always_inline)) inline void sign_bits(const double (&lv)[kNE], const double (&ll)[kNE], int eg, bool owner, int bits, int& code,
+                                 double& gap, double& vmax) {
     const bool mine = owner && eg < bits;
-    const unsigned long long set = __ballot(mine && lv[0] > 0.0);
+    const unsigned long long set = __ballot(mine && (lv[0] > 0.0 || (lv[0] == 0.0 && ll[0] > 0.0)));
     code = static_cast<int>(set & ((1ull << bits) - 1ull));
     double lo = mine ? fabs(lv[0]) : INFINITY, hi = mine ? fabs(lv[0]) : 0.0;
 #pragma unroll
@@ -103,7 +129,7 @@ __device__ inline void sign_bits(const double (&lv)[kNE], int eg, bool owner, in
 }
 
 // Smallest gap between consecutive ranks 0..kk-1 and the largest magnitude among them.
-__device__ inline void rank_gaps(const double (&sv)[kSel], int kk, double& gap, double& vmax) {
+__device__ __attribute__((always_inline)) inline void rank_gaps(const double (&sv)[kSel], int kk, double& gap, double& vmax) {
     gap = INFINITY;
     vmax = 0.0;
 #pragma unroll
@@ -212,17 +238,17 @@ __global__ __launch_bounds__(kWaves * 64) void route_kernel(const XT* __restrict
     for (int tt = 0; tt < kTPW; ++tt) {
         const int t = t0 + tt;
         if (t >= T) continue;
-        double lv[kNE];
+        double lv[kNE], ll[kNE];                // logits as pairs (value, low part); the low part is 0 for fp32 logits
 #pragma unroll
-        for (int i = 0; i < kNE; ++i) lv[i] = static_cast<double>(tot[tt][i] + bl[i]);
+        for (int i = 0; i < kNE; ++i) { lv[i] = static_cast<double>(tot[tt][i] + bl[i]); ll[i] = 0.0; }
         double sv[kSel];
         int se[kSel];
         int code = 0;
         double vmax, gap;
         if (hash) {
-            sign_bits(lv, eg, owner, E, code, gap, vmax);
+            sign_bits(lv, ll, eg, owner, E, code, gap, vmax);
         } else {
-            wave_topk(lv, eg, owner, E, kk_sel, sv, se);
+            wave_topk(lv, ll, eg, owner, E, kk_sel, sv, se);
             rank_gaps(sv, kk_sel, gap, vmax);
         }
         // |computed - exact| <= n_round u |x_t| |W_g col| + u |logit| for every logit that matters
@@ -230,25 +256,33 @@ __global__ __launch_bounds__(kWaves * 64) void route_kernel(const XT* __restrict
         const double delta = 1.0625 * 5.9604644775390625e-8 *
                              (static_cast<double>(n_round) * sqrt(static_cast<double>(xsq[tt]) * static_cast<double>(wn2)) + vmax);
         if (gap <= 2.0 * delta) {
-            // too close to call in fp32: exact products, fp64 sums
-            double acc[kNE];
+            // too close to call in fp32: exact products, sums in twice the fp64 precision
+            double acc[kNE], low[kNE];
 #pragma unroll
-            for (int i = 0; i < kNE; ++i) acc[i] = 0.0;
+            for (int i = 0; i < kNE; ++i) { acc[i] = 0.0; low[i] = 0.0; }
             for (int kk = ks; kk < d; kk += KS) {
                 const double xv = static_cast<double>(ldf(x, xrow[tt] + kk));
 #pragma unroll
                 for (int i = 0; i < kNE; ++i) {
                     const int ei = eg + 64 * i;
-                    if (ei < E) acc[i] = fma(xv, static_cast<double>(ldf(Wg, static_cast<size_t>(kk) * E + ei)), acc[i]);
+                    if (ei < E) dd_add_product(acc[i], low[i], xv, static_cast<double>(ldf(Wg, static_cast<size_t>(kk) * E + ei)));
                 }
             }
             for (int off = EP; off < 64; off <<= 1)
 #pragma unroll
-                for (int i = 0; i < kNE; ++i) acc[i] += __shfl_xor(acc[i], off);
+                for (int i = 0; i < kNE; ++i) {
+                    const double oh = __shfl_xor(acc[i], off), ol = __shfl_xor(low[i], off);
+                    dd_add(acc[i], low[i], oh, ol);
+                }
 #pragma unroll
-            for (int i = 0; i < kNE; ++i) lv[i] = acc[i] + static_cast<double>(bl[i]);
-            if (hash) sign_bits(lv, eg, owner, E, code, gap, vmax);
-            else wave_topk(lv, eg, owner, E, kk_sel, sv, se);
+            for (int i = 0; i < kNE; ++i) {
+                dd_add(acc[i], low[i], static_cast<double>(bl[i]), 0.0);
+                dd_normalise(acc[i], low[i]);
+                lv[i] = acc[i];
+                ll[i] = low[i];
+            }
+            if (hash) sign_bits(lv, ll, eg, owner, E, code, gap, vmax);
+            else wave_topk(lv, ll, eg, owner, E, kk_sel, sv, se);
         }
         if (hash) {
             if (lane == 0) { idx[t] = code; w[t] = 1.f; }
@@ -350,13 +384,16 @@ __device__ inline float from_order_key(unsigned key) {
     return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
 }
 
-// Exact value (products exact, sums in fp64) of column `col` of the projection of token t, by one wave, from
-// the packed fragments: lane j takes the 8-row pieces j, j + 64, ... of the column.  Every lane gets the sum.
-__device__ inline double exact_column_dot(const uint16_t* __restrict__ x, const uint4* __restrict__ pack, size_t t, int col,
-                                          int nS, int d, int lane) {
+// Value of column `col` of the projection of token t from exact products, by one wave, from the packed fragments:
+// lane j takes the 8-row pieces j, j + 64, ... of the column.  PAIR = false: plain fp64 sums (error at most about
+// d 2^-53 |x_t| |column|), lo = 0.  PAIR = true: sums in twice that precision, the pair (hi, lo) not yet normalised;
+// only needed when fp64 leaves candidates closer than its own error.  Every lane gets the sum.
+template <bool PAIR>
+__device__ __attribute__((always_inline)) inline void exact_column_dot(const uint16_t* __restrict__ x, const uint4* __restrict__ pack, size_t t,
+                                                           int col, int nS, int d, int lane, double& hi, double& lo) {
     const int nb = col >> 5, cin = col & 31;
     const uint4* xr = reinterpret_cast<const uint4*>(x + t * d);
-    double sum = 0.0;
+    double sum = 0.0, low = 0.0;
     for (int j = lane; j < nS * 8; j += 64) {
         const int S = j >> 3, q = (j & 7) >> 1, h = j & 1;          // rows 64 S + 32 h + 8 q .. + 8
         const uint4 wq = pack[((static_cast<size_t>(nb) * nS + S) * 4 + q) * 64 + h * 32 + cin];
@@ -364,14 +401,29 @@ __device__ inline double exact_column_dot(const uint16_t* __restrict__ x, const 
         const uint32_t xu[4] = {xq.x, xq.y, xq.z, xq.w}, wu[4] = {wq.x, wq.y, wq.z, wq.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            sum = fma(static_cast<double>(__uint_as_float(xu[i] << 16)), static_cast<double>(__uint_as_float(wu[i] << 16)), sum);
-            sum = fma(static_cast<double>(__uint_as_float(xu[i] & 0xffff0000u)),
-                      static_cast<double>(__uint_as_float(wu[i] & 0xffff0000u)), sum);
+            const double x0 = static_cast<double>(__uint_as_float(xu[i] << 16)), w0 = static_cast<double>(__uint_as_float(wu[i] << 16));
+            const double x1 = static_cast<double>(__uint_as_float(xu[i] & 0xffff0000u)), w1 = static_cast<double>(__uint_as_float(wu[i] & 0xffff0000u));
+            if constexpr (PAIR) {
+                dd_add_product(sum, low, x0, w0);
+                dd_add_product(sum, low, x1, w1);
+            } else {
+                sum = fma(x0, w0, sum);
+                sum = fma(x1, w1, sum);
+            }
         }
     }
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
-    return sum;
+    for (int off = 32; off >= 1; off >>= 1) {
+        const double oh = __shfl_xor(sum, off);
+        if constexpr (PAIR) {
+            const double ol = __shfl_xor(low, off);
+            dd_add(sum, low, oh, ol);
+        } else {
+            sum += oh;
+        }
+    }
+    hi = sum;
+    lo = low;
 }
 
 constexpr int kMaxCand = 12;     // columns of one token that are re-evaluated one by one; more than that: all columns
@@ -398,7 +450,7 @@ __global__ __launch_bounds__(kGateWaves * 64, (TOK == 32 && NB == 1) ? 4 : 2) vo
     __shared__ float xsq_w[kGateWaves][kGateTokens];
     __shared__ float wn2_sh;
     __shared__ int flagged[kGateTokens];
-    __shared__ double resc[kGateWaves][EP];
+    __shared__ double resc[kGateWaves][EP], resc_lo[kGateWaves][EP];    // re-evaluated logits per wave: value and low part
     auto tile_at = [&](int p, int tok, int e) -> float& { return part_tile[(p * kGateTokens + tok) * (EP + 1) + e]; };
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -557,15 +609,15 @@ __global__ __launch_bounds__(kGateWaves * 64, (TOK == 32 && NB == 1) ? 4 : 2) vo
             fv[i] = ei < E ? (sum + bl[i]) + 0.0f : 0.f;
             key[i] = ei < E ? order_key(fv[i]) : 0u;
         }
-        double lv[kNE];                          // entries from NE on belong to no expert and are never looked at
+        double lv[kNE], ll[kNE];                 // (value, low part); entries from NE on belong to no expert and are never looked at
 #pragma unroll
-        for (int i = 0; i < kNE; ++i) lv[i] = i < NE ? static_cast<double>(fv[i < NE ? i : 0]) : 0.0;
+        for (int i = 0; i < kNE; ++i) { lv[i] = i < NE ? static_cast<double>(fv[i < NE ? i : 0]) : 0.0; ll[i] = 0.0; }
         double sv[kSel];
         int se[kSel];
         int code = 0;
         double gap, vmax;
         if (hash) {
-            sign_bits(lv, eg, true, E, code, gap, vmax);
+            sign_bits(lv, ll, eg, true, E, code, gap, vmax);
         } else {
             // rank by rank: the largest key of the wave, then the lowest expert that has it
             unsigned taken = 0;
@@ -637,21 +689,38 @@ __global__ __launch_bounds__(kGateWaves * 64, (TOK == 32 && NB == 1) ? 4 : 2) vo
         }
         if (lane == 0) flagged[tt] = count > kMaxCand ? 1 : 0;
         if (count > kMaxCand) continue;                                  // all columns, by the whole block, below
+        // the columns in reach from exact products: in fp64 first, and once more in twice that precision if that
+        // still leaves the decision inside the rounding error (in practice: exact ties)
+        auto evaluate = [&](auto pair) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < NE; ++i) {
-            unsigned long long m = in_reach[i];
-            while (m != 0ull) {                                          // uniform for the wave
-                const int l = __ffsll(static_cast<long long>(m)) - 1;
-                m &= m - 1ull;
-                const double exact = exact_column_dot(x, pack, static_cast<size_t>(t), l + 64 * i, nS, d, lane);
-                if (eg == l) lv[i] = exact + static_cast<double>(bl[i]);
+            for (int i = 0; i < NE; ++i) {
+                unsigned long long m = in_reach[i];
+                while (m != 0ull) {                                      // uniform for the wave
+                    const int l = __ffsll(static_cast<long long>(m)) - 1;
+                    m &= m - 1ull;
+                    double hi, lo;
+                    exact_column_dot<decltype(pair)::value>(x, pack, static_cast<size_t>(t), l + 64 * i, nS, d, lane, hi, lo);
+                    if (eg == l) {
+                        dd_add(hi, lo, static_cast<double>(bl[i]), 0.0);
+                        dd_normalise(hi, lo);
+                        lv[i] = hi;
+                        ll[i] = decltype(pair)::value ? lo : 0.0;
+                    }
+                }
             }
-        }
+            if (hash) {
+                sign_bits(lv, ll, eg, true, E, code, gap, vmax);
+            } else {
+                wave_topk(lv, ll, eg, true, E, kk_sel, sv, se);
+                rank_gaps(sv, kk_sel, gap, vmax);
+            }
+        };
+        evaluate(std::false_type{});
+        const double delta64 = 1.0625 * 1.1102230246251565e-16 * (static_cast<double>(d + 8) * sqrt(xn2 * wn2) + 2.0 * vmax);
+        if (gap <= 2.0 * delta64) evaluate(std::true_type{});
         if (hash) {
-            sign_bits(lv, eg, true, E, code, gap, vmax);
             if (lane == 0) { idx[t] = code; w[t] = 1.f; }
         } else {
-            wave_topk(lv, eg, true, E, kk_sel, sv, se);
             emit_token(lv, sv, se, eg, true, E, k, renorm, lane, idx + static_cast<size_t>(t) * k, w + static_cast<size_t>(t) * k);
         }
     }
@@ -667,9 +736,9 @@ __global__ __launch_bounds__(kGateWaves * 64, (TOK == 32 && NB == 1) ? 4 : 2) vo
         todo &= todo - 1ull;
         const int t = t0 + tt;
         const uint4* xr = reinterpret_cast<const uint4*>(x + static_cast<size_t>(t) * d + 32 * (lane >> 5));
-        double a64[NB];
+        double a64[NB], l64[NB];
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) a64[nb] = 0.0;
+        for (int nb = 0; nb < NB; ++nb) { a64[nb] = 0.0; l64[nb] = 0.0; }
         for (int S = wave; S < nS; S += kGateWaves) {
             uint4 xa[4];
 #pragma unroll
@@ -686,38 +755,44 @@ __global__ __launch_bounds__(kGateWaves * 64, (TOK == 32 && NB == 1) ? 4 : 2) vo
                     const uint32_t wu[4] = {wb[q].x, wb[q].y, wb[q].z, wb[q].w};
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        a64[nb] = fma(static_cast<double>(__uint_as_float(xu[i] << 16)),
-                                      static_cast<double>(__uint_as_float(wu[i] << 16)), a64[nb]);
-                        a64[nb] = fma(static_cast<double>(__uint_as_float(xu[i] & 0xffff0000u)),
-                                      static_cast<double>(__uint_as_float(wu[i] & 0xffff0000u)), a64[nb]);
+                        dd_add_product(a64[nb], l64[nb], static_cast<double>(__uint_as_float(xu[i] << 16)),
+                                       static_cast<double>(__uint_as_float(wu[i] << 16)));
+                        dd_add_product(a64[nb], l64[nb], static_cast<double>(__uint_as_float(xu[i] & 0xffff0000u)),
+                                       static_cast<double>(__uint_as_float(wu[i] & 0xffff0000u)));
                     }
                 }
             }
         }
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            a64[nb] += __shfl_xor(a64[nb], 32);
-            if (lane < 32) resc[wave][32 * nb + lane] = a64[nb];
+            const double oh = __shfl_xor(a64[nb], 32), ol = __shfl_xor(l64[nb], 32);
+            dd_add(a64[nb], l64[nb], oh, ol);
+            if (lane < 32) { resc[wave][32 * nb + lane] = a64[nb]; resc_lo[wave][32 * nb + lane] = l64[nb]; }
         }
         __syncthreads();
         if (wave == 0) {
-            double lv[kNE];
+            double lv[kNE], ll[kNE];
 #pragma unroll
             for (int i = 0; i < kNE; ++i) {
                 const int ei = eg + 64 * i;
-                double sum = ei < E ? resc[0][ei] : 0.0;
-                for (int wv = 1; wv < kGateWaves; ++wv) sum += ei < E ? resc[wv][ei] : 0.0;
-                lv[i] = ei < E ? sum + static_cast<double>(bl[i]) : 0.0;
+                double sum = 0.0, low = 0.0;
+                if (ei < E) {
+                    for (int wv = 0; wv < kGateWaves; ++wv) dd_add(sum, low, resc[wv][ei], resc_lo[wv][ei]);
+                    dd_add(sum, low, static_cast<double>(bl[i]), 0.0);
+                    dd_normalise(sum, low);
+                }
+                lv[i] = sum;
+                ll[i] = low;
             }
             if (hash) {
                 int code;
                 double gap, vmax;
-                sign_bits(lv, eg, true, E, code, gap, vmax);
+                sign_bits(lv, ll, eg, true, E, code, gap, vmax);
                 if (lane == 0) { idx[t] = code; w[t] = 1.f; }
             } else {
                 double sv[kSel];
                 int se[kSel];
-                wave_topk(lv, eg, true, E, kk_sel, sv, se);
+                wave_topk(lv, ll, eg, true, E, kk_sel, sv, se);
                 emit_token(lv, sv, se, eg, true, E, k, renorm, lane, idx + static_cast<size_t>(t) * k, w + static_cast<size_t>(t) * k);
             }
         }

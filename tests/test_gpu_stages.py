@@ -103,6 +103,60 @@ def test_route_ties_and_near_ties(dtype):
     assert (ref.margin < 1e-6).sum() >= 2
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("E,k,twins", [(12, 3, 2), (40, 2, 20)])
+def test_route_ties_between_different_columns(dtype, E, k, twins):
+    """Columns that are not the same and still give exactly the same projection for every token (entries i and j
+    swapped, and the tokens have x_i = x_j): a tie in exact arithmetic, which sums rounded in different orders
+    need not notice.  The gate must take it for a tie (lower expert first), few twins (one by one) and many (the
+    block-wide pass) alike, and with a bias that breaks the tie by one unit in the last place of an fp32 it must
+    follow the bias."""
+    T, d = 90, 256
+    x, Wg, _ = make_inputs(17, T, d, E, dtype)
+    i, j = 5, 201
+    first = 3
+    pairs = [((i + 7 * n) % d, (j + 11 * n) % d) for n in range(1, twins)]
+    for a, b in pairs:                            # every token has the same value in all coordinates that get swapped
+        x[:, a] = x[:, i]
+        x[:, b] = x[:, i]
+    for n, (a, b) in enumerate(pairs, 1):         # twins of column `first`: the same entries, two of them swapped
+        Wg[:, first + n] = Wg[:, first]
+        Wg[a, first + n], Wg[b, first + n] = Wg[b, first], Wg[a, first]
+    cfg = M.MoeCfg.make(T, d, 64, E, k, dtype)
+    idx, w = gpu_route(cfg, x, Wg, None, dtype)
+    ref = O.route(x, Wg, k)
+    assert np.array_equal(idx, ref.idx)
+    assert (idx == first).any()
+    for slot in range(k - 1):                     # wherever a twin is selected, the next slot holds the next twin
+        sel = (idx[:, slot] >= first) & (idx[:, slot] < first + twins - 1)
+        assert np.all(idx[sel, slot + 1] == idx[sel, slot] + 1)
+    bias = np.zeros(E, dtype=np.float32)
+    bias[first + 1] = np.float32(2.0 ** -20)      # now the second twin is ahead of the first, by far less than the fp32 noise
+    idx2, _ = gpu_route(cfg, x, Wg, bias, dtype)
+    ref2 = O.route(x, Wg, k, bias)
+    assert np.array_equal(idx2, ref2.idx)
+    sel = idx2[:, 0] == first + 1
+    assert sel.any() and np.all(idx2[sel, 1] == first)
+
+
+def test_route_gap_far_below_the_last_place_of_an_fp64_logit():
+    """fp32 inputs: two columns whose exact projections differ by 2^-83 of their size: an fp64 sum cannot tell them
+    apart; the pair arithmetic of the re-evaluation can, and the higher-numbered expert, which is ahead, comes first."""
+    T, d, E, k = 40, 128, 6, 2
+    x, Wg, _ = make_inputs(23, T, d, E, "f32")
+    x[:, 9] = np.float32(2.0 ** -60)
+    Wg[:, 4] = Wg[:, 1]
+    Wg[9, 1] = np.float32(1.0)
+    Wg[9, 4] = np.float32(1.0 + 2.0 ** -23)
+    cfg = M.MoeCfg.make(T, d, 64, E, k, "f32")
+    idx, w = gpu_route(cfg, x, Wg, None, "f32")
+    ref = O.route(x, Wg, k)
+    assert np.array_equal(idx, ref.idx)
+    sel = idx[:, 0] == 4
+    assert sel.any() and np.all(idx[sel, 1] == 1) and not (idx[:, 0] == 1).any()
+    assert 0.0 < ref.margin.min() < 1e-24
+
+
 @pytest.mark.parametrize("E,k", [(40, 2), (200, 8)])
 def test_route_many_columns_too_close_to_call(E, k):
     """More tied columns than the gate re-evaluates one by one (twenty identical experts, and tokens that are
