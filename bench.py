@@ -41,6 +41,9 @@ def parse():
                     help="resident c3 run: leave out the short host-streamed leg (T 512, the same weights) that fills the "
                          "'streaming' record")
     ap.add_argument("--no-graph", action="store_true", help="resident run: leave out the captured-graph replay")
+    ap.add_argument("--no-mfma-leg", action="store_true",
+                    help="resident c3 run: leave out the short leg at T 65536 on the same experts (2048 tokens per expert: the "
+                         "regime bound by the matrix cores), which fills the 'mfma_leg' record")
     ap.add_argument("--tokens", type=int, default=None,
                     help="run the workload's layer on this many tokens instead of its own count (a sweep over batch sizes; "
                          "the figure the workload is quoted on is the one without this option)")
@@ -481,6 +484,39 @@ def main():
                             "note": "the same layer call captured once in a HIP graph and replayed; value/ms_per_step above "
                                     "are the eager launches"}
             del g
+        if args.workload == "c3" and args.tokens is None and not args.no_mfma_leg:
+            # "% of the MFMA peak" is only meaningful where the matrix cores bind: the same layer and experts on a batch of
+            # 2^16 tokens (a fine-tuning batch of Section 4.1), every expert with about 2048 rows
+            wlm = wl.with_tokens(65536)
+            cfgm = H.cfg_of(wlm).with_packed_gate()
+            xm = H.to_device(W.gen_x(wlm), wlm.dtype)
+            wsm = torch.empty(M.moe_workspace_bytes(cfgm), dtype=torch.uint8, device="cuda")
+            ym = torch.empty((wlm.T, wlm.d), dtype=cfgm.torch_dtype, device="cuda")
+            for _ in range(3):
+                M.moe_layer_forward(cfgm, xm, gate, L.bias, L.packed, None, ym, wsm)
+            torch.cuda.synchronize()
+            n_m = 10
+            t1 = time.perf_counter()
+            for _ in range(n_m):
+                M.moe_layer_forward(cfgm, xm, gate, L.bias, L.packed, None, ym, wsm)
+            torch.cuda.synchronize()
+            m_ms = (time.perf_counter() - t1) * 1e3 / n_m
+            tm = M.Timer(4, M.TIME_STAGES)
+            for _ in range(4):
+                M.moe_layer_forward_timed(cfgm, xm, gate, L.bias, L.packed, ym, wsm, tm)
+            torch.cuda.synchronize()
+            st = tm.read()
+            tm.close()
+            upm = float(np.mean([c["ffn_up"] for c in st]))
+            dnm = float(np.mean([c["ffn_down"] for c in st]))
+            fl = 6.0 * d * f * wlm.A
+            out["mfma_leg"] = {"workload": wlm.name, "T": wlm.T, "steps": n_m, "ms_per_step": m_ms, "tokens_per_s": wlm.T / (m_ms * 1e-3),
+                               "ffn_up_ms": upm, "ffn_down_ms": dnm, "ffn_tflops": fl / ((upm + dnm) * 1e-3) / 1e12,
+                               "mfma_frac": fl / ((upm + dnm) * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                               "up_kernel_tflops": 4.0 * d * f * wlm.A / (upm * 1e-3) / 1e12, "peak_tflops": MFMA_BF16_PEAK_TFLOPS,
+                               "note": "the layer and experts of the run above on 65536 tokens; kernel times from 4 extra steps with "
+                                       "events between the stages (ffn_up includes the work-list kernel)"}
+            del xm, wsm, ym
         if streaming_leg:
             # the other half of the metric: the same layer and weights with host-streamed experts, on the short batch
             # of the streamed configuration (T 512); a few steps are enough, every step moves all 32 experts
