@@ -386,6 +386,60 @@ def main():
             dst.copy_(src)
             torch.cuda.synchronize()
             del src, dst
+        # The two short legs that fill the other halves of the metric run first, the host-streamed one (mostly copies)
+        # before the one at T 65536 (heavy matrix load), and the resident measurement follows at once: after an idle
+        # spell (the set-up generates weights on the host for seconds) the first ten to twenty layer steps run 5-30 %
+        # slow while the GPU's power management settles, which a run of 5 warm-up and 20 timed steps would mostly
+        # measure; straight after the T 65536 leg the first steps already run at the steady rate.
+        if streaming_leg:
+            # the other half of the metric: the same layer and weights with host-streamed experts, on the short batch
+            # of the streamed configuration (T 512); a few steps are enough, every step moves all 32 experts
+            wls = W.CONFIGS["c4a"]
+            cfgs = H.cfg_of(wls).with_packed_gate()
+            xs = H.to_device(W.gen_x(wls), wls.dtype)
+            wss = torch.empty(M.moe_workspace_bytes(cfgs), dtype=torch.uint8, device="cuda")
+            ys = torch.empty((wls.T, wls.d), dtype=cfgs.torch_dtype, device="cuda")
+            _, sroof, srec, _ = streamed_leg(M, torch, np, cfgs, xs, gate, None, L.host_packed, ys, wss, wls, 5, 2,
+                                             args.slots)
+            srec["roofline"] = sroof
+            out["streaming"] = srec
+        if args.workload == "c3" and args.tokens is None and not args.no_mfma_leg:
+            # "% of the MFMA peak" is only meaningful where the matrix cores bind: the same layer and experts on a batch of
+            # 2^16 tokens (a fine-tuning batch of Section 4.1), every expert with about 2048 rows
+            wlm = wl.with_tokens(65536)
+            cfgm = H.cfg_of(wlm).with_packed_gate()
+            xm = H.to_device(W.gen_x(wlm), wlm.dtype)
+            wsm = torch.empty(M.moe_workspace_bytes(cfgm), dtype=torch.uint8, device="cuda")
+            ym = torch.empty((wlm.T, wlm.d), dtype=cfgm.torch_dtype, device="cuda")
+            for _ in range(3):
+                M.moe_layer_forward(cfgm, xm, gate, L.bias, L.packed, None, ym, wsm)
+            torch.cuda.synchronize()
+            n_m = 10
+            t1 = time.perf_counter()
+            for _ in range(n_m):
+                M.moe_layer_forward(cfgm, xm, gate, L.bias, L.packed, None, ym, wsm)
+            torch.cuda.synchronize()
+            m_ms = (time.perf_counter() - t1) * 1e3 / n_m
+            tm = M.Timer(4, M.TIME_STAGES)
+            for _ in range(4):
+                M.moe_layer_forward_timed(cfgm, xm, gate, L.bias, L.packed, ym, wsm, tm)
+            torch.cuda.synchronize()
+            st = tm.read()
+            tm.close()
+            upm = float(np.mean([c["ffn_up"] for c in st]))
+            dnm = float(np.mean([c["ffn_down"] for c in st]))
+            fl = 6.0 * d * f * wlm.A
+            out["mfma_leg"] = {"workload": wlm.name, "T": wlm.T, "steps": n_m, "ms_per_step": m_ms, "tokens_per_s": wlm.T / (m_ms * 1e-3),
+                               "ffn_up_ms": upm, "ffn_down_ms": dnm, "ffn_tflops": fl / ((upm + dnm) * 1e-3) / 1e12,
+                               "mfma_frac": fl / ((upm + dnm) * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                               "up_kernel_tflops": 4.0 * d * f * wlm.A / (upm * 1e-3) / 1e12, "peak_tflops": MFMA_BF16_PEAK_TFLOPS,
+                               "note": "the layer and experts of the run above on 65536 tokens; kernel times from 4 extra steps with "
+                                       "events between the stages (ffn_up includes the work-list kernel)"}
+            del xm, wsm, ym
+        if "mfma_leg" in out:
+            out["order_note"] = ("the streaming and mfma legs ran before the warm-up and timed steps of the resident measurement "
+                                 "(GPU under load when the warm-up starts); with them after it, the first steps after the idle "
+                                 "set-up run slow and 20 timed steps after 5 warm-up steps measure about 3 % more per step")
         for _ in range(args.warmup):
             step()
         torch.cuda.synchronize()
@@ -484,51 +538,6 @@ def main():
                             "note": "the same layer call captured once in a HIP graph and replayed; value/ms_per_step above "
                                     "are the eager launches"}
             del g
-        if args.workload == "c3" and args.tokens is None and not args.no_mfma_leg:
-            # "% of the MFMA peak" is only meaningful where the matrix cores bind: the same layer and experts on a batch of
-            # 2^16 tokens (a fine-tuning batch of Section 4.1), every expert with about 2048 rows
-            wlm = wl.with_tokens(65536)
-            cfgm = H.cfg_of(wlm).with_packed_gate()
-            xm = H.to_device(W.gen_x(wlm), wlm.dtype)
-            wsm = torch.empty(M.moe_workspace_bytes(cfgm), dtype=torch.uint8, device="cuda")
-            ym = torch.empty((wlm.T, wlm.d), dtype=cfgm.torch_dtype, device="cuda")
-            for _ in range(3):
-                M.moe_layer_forward(cfgm, xm, gate, L.bias, L.packed, None, ym, wsm)
-            torch.cuda.synchronize()
-            n_m = 10
-            t1 = time.perf_counter()
-            for _ in range(n_m):
-                M.moe_layer_forward(cfgm, xm, gate, L.bias, L.packed, None, ym, wsm)
-            torch.cuda.synchronize()
-            m_ms = (time.perf_counter() - t1) * 1e3 / n_m
-            tm = M.Timer(4, M.TIME_STAGES)
-            for _ in range(4):
-                M.moe_layer_forward_timed(cfgm, xm, gate, L.bias, L.packed, ym, wsm, tm)
-            torch.cuda.synchronize()
-            st = tm.read()
-            tm.close()
-            upm = float(np.mean([c["ffn_up"] for c in st]))
-            dnm = float(np.mean([c["ffn_down"] for c in st]))
-            fl = 6.0 * d * f * wlm.A
-            out["mfma_leg"] = {"workload": wlm.name, "T": wlm.T, "steps": n_m, "ms_per_step": m_ms, "tokens_per_s": wlm.T / (m_ms * 1e-3),
-                               "ffn_up_ms": upm, "ffn_down_ms": dnm, "ffn_tflops": fl / ((upm + dnm) * 1e-3) / 1e12,
-                               "mfma_frac": fl / ((upm + dnm) * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                               "up_kernel_tflops": 4.0 * d * f * wlm.A / (upm * 1e-3) / 1e12, "peak_tflops": MFMA_BF16_PEAK_TFLOPS,
-                               "note": "the layer and experts of the run above on 65536 tokens; kernel times from 4 extra steps with "
-                                       "events between the stages (ffn_up includes the work-list kernel)"}
-            del xm, wsm, ym
-        if streaming_leg:
-            # the other half of the metric: the same layer and weights with host-streamed experts, on the short batch
-            # of the streamed configuration (T 512); a few steps are enough, every step moves all 32 experts
-            wls = W.CONFIGS["c4a"]
-            cfgs = H.cfg_of(wls).with_packed_gate()
-            xs = H.to_device(W.gen_x(wls), wls.dtype)
-            wss = torch.empty(M.moe_workspace_bytes(cfgs), dtype=torch.uint8, device="cuda")
-            ys = torch.empty((wls.T, wls.d), dtype=cfgs.torch_dtype, device="cuda")
-            _, sroof, srec, _ = streamed_leg(M, torch, np, cfgs, xs, gate, None, L.host_packed, ys, wss, wls, 5, 2,
-                                             args.slots)
-            srec["roofline"] = sroof
-            out["streaming"] = srec
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, counts)
     print(json.dumps(out))
