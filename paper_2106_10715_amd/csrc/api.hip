@@ -387,11 +387,18 @@ int layer_forward(const moe_cfg* cfg, const void* x, const void* W_g, const floa
     if (int rc = launch_route(c, x, W_g, gate_bias, idx, w, base + L.route, s)) return rc;
     if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[1], s));
     bool planned = false;          // resident mode: the work list of the one FFN launch may come from the batching kernel
+    int plan_rows_down = ffn_tile_rows(gather_rows);      // (resident mode) the tile heights of the launch over all experts
+    if (sctx == nullptr && c.dtype == MOE_BF16) {
+        int dev = 0;
+        const DeviceInfo* info = nullptr;
+        if (int rc = device_info(&dev, &info)) return rc;
+        plan_rows_down = ffn_down_tile_rows(c, c.E, A, ffn_tile_rows(gather_rows), info->compute_units);
+    }
     if (int rc = launch_permute(c, x, idx, counts, offsets, perm, inv, gather_rows ? nullptr : base + L.Xp,
                                 reinterpret_cast<int32_t*>(base + L.chunk_hist), s,
                                 sctx == nullptr ? reinterpret_cast<int32_t*>(base + L.ffn_plan) : nullptr,
                                 static_cast<int>(ffn_plan_tiles(c)), sctx == nullptr ? &planned : nullptr,
-                                ffn_tile_rows(gather_rows)))
+                                ffn_tile_rows(gather_rows), plan_rows_down))
         return rc;
     if (all_stages) MOE_HIP_CHECK(hipEventRecord(tev[2], s));
 

@@ -75,7 +75,8 @@ size_t gate_packed_bytes(const moe_cfg& c);
 int launch_pack_gate(const moe_cfg& c, const void* Wg, void* packed, hipStream_t s);
 int launch_permute(const moe_cfg& c, const void* x, const int32_t* idx, int32_t* counts, int32_t* offsets,
                    int32_t* perm, int32_t* inv, void* Xp, int32_t* chunk_hist, hipStream_t s, int32_t* plan = nullptr,
-                   int plan_max_tiles = 0, bool* planned = nullptr, int plan_tile_rows = kTileM);
+                   int plan_max_tiles = 0, bool* planned = nullptr, int plan_tile_rows = kTileM,
+                   int plan_tile_rows_down = kTileM);
 // plan/planned: for short bf16 batches the kernel that batches the tokens also writes the work list of the expert
 // FFN launch over all experts that follows (room for plan_max_tiles row tiles) and sets *planned; the caller then
 // passes plan_ready to launch_expert_ffn.
@@ -99,6 +100,9 @@ int launch_expert_ffn(const moe_cfg& c, const void* Xp, const int32_t* offsets, 
 // ffn_tile_rows(true) rows high instead of ffn_tile_rows(false), and a work list written elsewhere (plan_ready) must
 // have been cut to that height.
 int ffn_tile_rows(bool gather);
+// Height of the down-projection's row tiles for a launch over e_count experts with at most max_rows rows in all (the two
+// kernels have a tile list each); n_cu: compute units of the device.
+int ffn_down_tile_rows(const moe_cfg& c, int e_count, long max_rows, int tile_m_up, int n_cu);
 // row_map (bf16 only): row r of the batched order is written to row row_map[r] of Yp instead of row r, which
 // turns the down-projection's output into the layer's output when no weighting follows (see moe_layer_forward).
 // `plan`: ffn_plan_bytes(c) bytes of workspace, rewritten by every launch_expert_ffn (room for ffn_plan_tiles(c) row tiles).

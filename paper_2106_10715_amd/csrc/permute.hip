@@ -139,7 +139,7 @@ __global__ __launch_bounds__(kSmallWaves * 64) void permute_small_kernel(const i
                                                                          int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
                                                                          int32_t* __restrict__ perm, int32_t* __restrict__ inv,
                                                                          int32_t* __restrict__ plan, int plan_max_tiles,
-                                                                         int plan_tile_rows) {
+                                                                         int plan_tile_rows, int plan_tile_rows_down) {
     __shared__ int run[256];                       // histogram, then the next free row of each expert
     __shared__ int wcnt[kSmallWaves][256];         // per wave, rows each expert takes in the current round
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -176,7 +176,11 @@ __global__ __launch_bounds__(kSmallWaves * 64) void permute_small_kernel(const i
     // the work list of the expert kernels that follow, when the caller wants it from here (saves a launch)
     if (plan != nullptr) {
         int (&scratch)[4][256] = reinterpret_cast<int (&)[4][256]>(wcnt);      // not in use yet; cleared again below
-        ffn_plan_block(offsets, 0, E, plan_tile_rows, plan, A, plan_max_tiles, scratch);
+        ffn_plan_block(offsets, 0, E, plan_tile_rows, plan, A, plan_max_tiles, scratch, 0);
+        if (plan_tile_rows_down != plan_tile_rows) {        // else the down kernel reads the up kernel's list
+            __syncthreads();
+            ffn_plan_block(offsets, 0, E, plan_tile_rows_down, plan, A, plan_max_tiles, scratch, 1);
+        }
         __syncthreads();
         if (threadIdx.x < 256) {
 #pragma unroll
@@ -236,14 +240,14 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restric
 
 int launch_permute(const moe_cfg& c, const void* x, const int32_t* idx, int32_t* counts, int32_t* offsets,
                    int32_t* perm, int32_t* inv, void* Xp, int32_t* chunk_hist, hipStream_t s, int32_t* plan,
-                   int plan_max_tiles, bool* planned, int plan_tile_rows) {
+                   int plan_max_tiles, bool* planned, int plan_tile_rows, int plan_tile_rows_down) {
     if (planned != nullptr) *planned = false;
     const int A = c.T * c.k;
     const int chunks = (A + kPermChunk - 1) / kPermChunk;
     if (A <= kSmallMaxA) {
         const bool with_plan = plan != nullptr && planned != nullptr && c.dtype == MOE_BF16 && A > 0;
         hipLaunchKernelGGL(permute_small_kernel, dim3(1), dim3(kSmallWaves * 64), 0, s, idx, A, c.E, counts, offsets, perm, inv,
-                           with_plan ? plan : nullptr, plan_max_tiles, plan_tile_rows);
+                           with_plan ? plan : nullptr, plan_max_tiles, plan_tile_rows, plan_tile_rows_down);
         MOE_LAUNCH_CHECK("permute_small_kernel");
         if (with_plan) *planned = true;
     } else {

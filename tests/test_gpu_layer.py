@@ -54,6 +54,8 @@ MID = [
     W.Workload("one-expert", T=130, d=128, f=128, E=1, k=1, dtype="bf16", seed=24),
     W.Workload("hash-gate-bf16", T=600, d=256, f=384, E=8, k=1, dtype="bf16", seed=25, gate="hash"),
     W.Workload("hash-gate-f32", T=90, d=128, f=256, E=4, k=1, dtype="f32", seed=26, gate="hash"),
+    # four experts of about 500 rows: the batching kernel writes two tile lists (the down-projection's tiles are lower)
+    W.Workload("few-experts-many-rows", T=2000, d=512, f=256, E=4, k=1, dtype="bf16", seed=27),
 ]
 
 

@@ -391,6 +391,8 @@ def run_ffn(T, d, f, E, k, dtype, counts, act=0, seed=0):
     (192, 320, 2, [129, 127], "bf16", 1),                    # tanh GELU
     (320, 128, 6, [0, 0, 64, 0, 0, 200], "f32", 1),
     (512, 1024, 3, [257, 128, 31], "bf16", 0),
+    (256, 384, 3, [700, 0, 310], "bf16", 0),                 # few experts of many rows: the down-projection's tiles are cut lower than the up-projection's
+    (1024, 256, 8, [250, 260, 241, 283, 256, 255, 257, 246], "bf16", 0),   # 8 experts of about a tile each: two down tiles per expert
 ])
 def test_expert_ffn_matches_oracle(d, f, E, counts, dtype, act):
     A = sum(counts)
