@@ -215,3 +215,29 @@ def test_gelu_tail_polynomial_of_the_ffn_kernel_is_accurate():
     near = a <= 4.0
     tail = 0.5 * erfc(a[near].astype(np.float64) / np.sqrt(2.0))
     assert np.abs(q[near] / tail - 1.0).max() <= 1e-3
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The layer is built and measured on one GPU; asked for more, the bench says so and exits without touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_gate_and_timer_arguments_are_checked_on_the_host():
+    cfg = M.MoeCfg.make(8, 64, 64, 4)
+    assert M.moe_gate_bytes(cfg) >= 64 * 32 * 2                  # columns padded to 32, plus the per-group sums of squares
+    assert M.moe_gate_bytes(M.MoeCfg.make(8, 64, 64, 4, dtype="f32")) >= 64 * 4 * 4
+    L = M.lib()
+    assert L.moe_pack_gate(C.byref(cfg), None, None, None) == -1 and b"W_g" in L.moe_last_error()
+    h = C.c_void_p(None)
+    assert L.moe_timer_create(0, 0, C.byref(h)) == -1 and b"max_calls" in L.moe_last_error()
+    assert L.moe_timer_create(4, 9, C.byref(h)) == -1 and b"mode" in L.moe_last_error()
+    assert L.moe_timer_destroy(None) == 0
+    assert L.moe_layer_forward_timed(C.byref(cfg), None, None, None, None, None, None, None, None) == -1
+    assert L.moe_stream_ctx_share_loader(None, None) == -1
+    # the batching entry point without a workspace refuses what its fixed array cannot hold, before touching anything
+    big = M.MoeCfg.make(262145, 64, 64, 4)
+    assert L.moe_permute_static(C.byref(big), None, C.c_void_p(8), C.c_void_p(8), C.c_void_p(8), C.c_void_p(8), C.c_void_p(8), None, None) == -3
+    assert b"262144" in L.moe_last_error()
