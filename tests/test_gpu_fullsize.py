@@ -246,3 +246,17 @@ def test_c6_token_throughput_regime_full_size():
     assert counts.min() > 1500                                       # every expert is in the compute-bound regime
     del L
     torch.cuda.empty_cache()
+
+
+def test_largest_batch_the_index_range_allows():
+    """T*k*d_ff just below 2^31 (the library's documented limit) on the 32-expert layer: 209715 tokens, a ragged last
+    block everywhere.  Integers in full, tile-seam rows and whole tokens against the oracle as for the other large workloads."""
+    wl = W.CONFIGS["c3"].with_tokens((2 ** 31 - 1) // 10240)
+    assert wl.T == 209715 and wl.T * wl.f < 2 ** 31 <= (wl.T + 1) * wl.f
+    L = H.build_layer(wl)
+    s = check_sampled(wl, L, n_experts=2, n_tokens=32)
+    assert int(s["offsets"][-1]) == wl.T
+    with pytest.raises(M.MoeError, match="2\\^31"):
+        M.moe_workspace_bytes(H.cfg_of(wl.with_tokens(wl.T + 1)))
+    del L, s
+    torch.cuda.empty_cache()
